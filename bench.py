@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the any-precision GEMV hot path on one MI355X.
+
+Workload (the configuration the headline metric is quoted on): the three linear-layer shapes of
+Llama-2-7B (4096x4096, 11008x4096, 4096x11008), 8-bit parent, batch 1, every bit-width b = 3..8.
+One step = one ap_gemv per (shape, b): 18 calls.  Inputs are seeded and synthetic (uniform 8-bit
+indices, sorted N(0, 0.02) binary16 tables, N(0, 1) binary16 activations) and resident in HBM
+before the timed region.  Every call of a step reads a different device copy of its matrix, and a
+copy is reused only after several hundred MB of other traffic, so the numbers are HBM-cold
+(neither the 256 MB last-level cache nor the L2 holds the data).
+
+Prints ONE JSON line: effective GB/s over the timed steps (algorithmic bytes / elapsed), with the
+roofline of the dominant kernel and the CPU oracle timed beside it.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+COPIES = 7      # device copies of every packed matrix (rotation period)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=210)
+    ap.add_argument("--warmup", type=int, default=21)
+    ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--detail", action="store_true", help="also print a per-(shape, b) table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2402_10517_amd import binding as B
+    from paper_2402_10517_amd import inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    shapes = inputs.CONFIGS[2]["shapes"]
+    bits = list(range(3, 9))
+
+    # ---- inputs resident in HBM -------------------------------------------------------------
+    cases = []
+    for (M, K) in shapes:
+        idx, luts, x = inputs.make_case(2, M, K)
+        pm = B.ap_pack(idx, luts, device=dev)
+        copies = [pm] + [pm.clone() for _ in range(COPIES - 1)]
+        xd = torch.from_numpy(x).to(dev)
+        yd = torch.empty((1, M), dtype=torch.float16, device=dev)
+        cases.append(dict(M=M, K=K, idx=idx, luts=luts, x=x, copies=copies, xd=xd, yd=yd))
+    stream = torch.cuda.current_stream()
+    sp = ctypes.c_void_p(stream.cuda_stream)
+
+    def issue_step(phase):
+        """The 18 calls of one step; `phase` selects which device copies they read."""
+        c = phase * len(bits)
+        for b in bits:
+            for cs in cases:
+                pm = cs["copies"][c % COPIES]
+                st = B.lib.ap_gemv(pm.handle, b, cs["xd"].data_ptr(), cs["yd"].data_ptr(), 1, sp)
+                if st != 0:
+                    raise RuntimeError("ap_gemv failed: %s" % B.strerror(st))
+            c += 1
+
+    step_bytes = sum(inputs.algorithmic_bytes(cs["M"], cs["K"], b) for cs in cases for b in bits)
+
+    graphs = None
+    if not args.no_graph:
+        # one captured graph per rotation phase; side stream as torch requires for capture
+        graphs = []
+        cap = torch.cuda.Stream()
+        for phase in range(COPIES):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(cap):
+                sp_save = sp
+                sp = ctypes.c_void_p(cap.cuda_stream)
+                issue_step(phase)          # eager warm-up on the capture stream
+                cap.synchronize()
+                with torch.cuda.graph(g, stream=cap):
+                    issue_step(phase)
+                sp = sp_save
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+    def run_step(i):
+        if graphs is not None:
+            graphs[i % COPIES].replay()
+        else:
+            issue_step(i % COPIES)
+
+    for i in range(args.warmup):
+        run_step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        run_step(args.warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms = e0.elapsed_time(e1)
+    ms_per_step = ms / args.steps
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-kernel durations, live, with events on the launch stream ---------------------------
+    # N back-to-back launches of one (shape, b) over rotating copies between two events; the average
+    # includes the dispatch gap between dependent launches, so it bounds the kernel time from above.
+    per_call = []
+    reps = 5 * COPIES
+    for b in bits:
+        for cs in cases:
+            for r in range(COPIES):
+                B.lib.ap_gemv(cs["copies"][r].handle, b, cs["xd"].data_ptr(), cs["yd"].data_ptr(), 1, sp)
+            torch.cuda.synchronize()
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            for r in range(reps):
+                B.lib.ap_gemv(cs["copies"][r % COPIES].handle, b, cs["xd"].data_ptr(), cs["yd"].data_ptr(), 1, sp)
+            a1.record()
+            torch.cuda.synchronize()
+            us = a0.elapsed_time(a1) * 1e3 / reps
+            nbytes = inputs.algorithmic_bytes(cs["M"], cs["K"], b)
+            per_call.append(dict(M=cs["M"], K=cs["K"], b=b, us=round(us, 3), bytes=nbytes,
+                                 GBps=round(nbytes / us / 1e3, 1),
+                                 frac_of_peak=round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)))
+    # dominant kernel = the bit-width whose launches take the most time in a step
+    by_b = {}
+    for pc in per_call:
+        d = by_b.setdefault(pc["b"], dict(us=0.0, bytes=0, n=0))
+        d["us"] += pc["us"]
+        d["bytes"] += pc["bytes"]
+        d["n"] += 1
+    dom_b = max(by_b, key=lambda k: by_b[k]["us"])
+    dom = by_b[dom_b]
+    achieved = dom["bytes"] / dom["us"] / 1e3
+    roofline = dict(bound="hbm", kernel="gemv_kernel<%d,1>" % dom_b, achieved=round(achieved, 1),
+                    peak=HBM_PEAK_GBPS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBPS, 4),
+                    bytes_per_launch=dom["bytes"] // dom["n"],
+                    avg_launch_us=round(dom["us"] / dom["n"], 3), traffic=None)
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload ----------------
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        cs = cases[0]
+        t_cpu, n_bytes, n_calls = 0.0, 0, 0
+        while t_cpu < 10.0 and n_calls < 60:
+            for b in bits:
+                t1 = time.perf_counter()
+                oracle.gemv(cs["idx"], cs["luts"][b], b, cs["x"])
+                t_cpu += time.perf_counter() - t1
+                n_bytes += inputs.algorithmic_bytes(cs["M"], cs["K"], b)
+                n_calls += 1
+        cpu = dict(value=round(n_bytes / t_cpu / 1e9, 4), unit="GB/s", cores=oracle.num_threads(),
+                   kind="oracle",
+                   sample="%d oracle calls on the 4096x4096 matrix, b=3..8 round robin, batch 1 (%.1f s)"
+                          % (n_calls, t_cpu),
+                   us_per_call=round(t_cpu / n_calls * 1e6, 1))
+
+    out = dict(metric="any-precision GEMV effective GB/s, b=3..8, batch 1 (HBM-cold)", value=round(value, 1),
+               unit="GB/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=round(ms_per_step, 5), higher_is_better=True, scaling="weak",
+               vs_baseline=None, dtype="f16 tables and activations, f32 accumulate", data="synthetic",
+               config=dict(workload="configs[1]: Llama-2-7B linears 4096x4096, 11008x4096, 4096x11008; "
+                                    "8-bit parent, b=3..8, batch 1; one step = 18 ap_gemv calls",
+                           calls_per_step=len(bits) * len(cases), bytes_per_step=step_bytes,
+                           device_copies=COPIES, launch="hip-graph" if graphs is not None else "python-loop"),
+               frac_of_hbm_peak=round(value / HBM_PEAK_GBPS, 4), us_per_call=round(ms_per_step * 1e3 / 18, 3),
+               wall_ms=round(wall_ms, 2), roofline=roofline, cpu_baseline=cpu, per_call=per_call)
+    if args.detail:
+        for pc in per_call:
+            print("  %5dx%-5d b=%d  %8.2f us  %7.1f GB/s  %5.1f%% of 8 TB/s" %
+                  (pc["M"], pc["K"], pc["b"], pc["us"], pc["GBps"], 100 * pc["frac_of_peak"]), file=sys.stderr)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

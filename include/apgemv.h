@@ -1,0 +1,125 @@
+/*
+ * apgemv - any-precision matrix-vector product for AMD MI355X (gfx950).
+ *
+ * One stored n-bit index per weight serves every b-bit model, 3 <= b <= n <= 8: a b-bit call
+ * uses the b most significant bits of each index and looks them up in the output channel's own
+ * table of 2^b binary16 centroids (Any-Precision LLM, Section 3.3 "Concept"; Section 4.1; the
+ * engine overview of Section 5.2).  The device layout is bit-sliced, so a b-bit call reads b bits
+ * per weight (Section 5.1, bitplane representation).
+ *
+ * Conventions: W is M x K, row = output channel; x is batch x K, y is batch x M, both row-major
+ * binary16 (the paper writes the product as (1,K) x (M,K), Table 6).  All functions return an
+ * ap_status; none throws, aborts or prints.  Every argument check happens before the first HIP
+ * call of a function, so the error paths need no GPU.  "host" and "device" below say where a
+ * pointer must point.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ */
+#ifndef APGEMV_H
+#define APGEMV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ap_matrix ap_matrix; /* opaque host-side handle of one packed matrix */
+
+typedef enum {
+    AP_OK = 0,
+    AP_ERR_INVALID_ARG = 1,      /* NULL pointer, misaligned buffer, bad handle */
+    AP_ERR_SHAPE = 2,            /* M < 1, K < 32 or K not a multiple of 32, sizes beyond 2^24 */
+    AP_ERR_BITS = 3,             /* n outside 3..8, b outside 3..n, or no table given for b */
+    AP_ERR_INDEX_RANGE = 4,      /* an index >= 2^n */
+    AP_ERR_BUFFER_TOO_SMALL = 5, /* destination smaller than ap_packed_size */
+    AP_ERR_BATCH = 6,            /* batch outside 1..8 */
+    AP_ERR_HIP = 7               /* a HIP runtime call or kernel launch failed */
+} ap_status;
+
+#define AP_MIN_BITS 3
+#define AP_MAX_BITS 8
+#define AP_MAX_BATCH 8
+#define AP_BLOB_ALIGN 256
+
+/*
+ * Bytes of the packed form of an M x K matrix with an n-bit parent and centroid tables for every
+ * b whose bit is set in lut_mask (bit b <=> b-bit model supported, 3 <= b <= n; Section 3.3: only
+ * the tables of the supported bit-widths are stored).  The packed form is position independent:
+ * a 256-byte header, then n bit slices of ceil(M/4)*4*K/8 bytes each, most significant slice
+ * first, then the tables, each region 256-byte aligned.
+ */
+ap_status ap_packed_size(int M, int K, int n, unsigned lut_mask, size_t *bytes);
+
+/*
+ * Host-only packing (no HIP call): split every n-bit index into bit slices in the device layout
+ * and append the centroid tables (Section 5.1 bitplanes; Section 5.3 layout pre-processing).
+ *   idx       host, M*K bytes row-major, every value < 2^n (else AP_ERR_INDEX_RANGE)
+ *   luts[b]   host, for 3 <= b <= n: M * 2^b binary16 bit patterns, entry e of row i at
+ *             [i*2^b + e]; NULL = b not supported.  luts[0..2] are ignored.  Tables need not be
+ *             sorted.  At least one table must be given.
+ *   blob      host, blob_bytes >= ap_packed_size(M, K, n, mask of non-NULL tables); written fully
+ */
+ap_status ap_pack_host(const uint8_t *idx, int M, int K, int n, const uint16_t *const luts[9],
+                       void *blob, size_t blob_bytes);
+
+/* Inverse of the index part of ap_pack_host: writes M*K index bytes (host) from a packed blob
+ * (host).  Bit-exact round trip is part of the contract. */
+ap_status ap_unpack_host(const void *blob, size_t blob_bytes, uint8_t *idx_out);
+
+/* Reads table entry e of row i for bit-width b back out of a packed blob (host): binary16 bits. */
+ap_status ap_blob_lut_entry(const void *blob, size_t blob_bytes, int b, int row, int entry,
+                            uint16_t *out);
+
+/*
+ * Byte range of the packed form that an ap_gemv call with bit-width b reads: the slice prefix
+ * [slices_begin, slices_end) and the table [lut_begin, lut_end), as offsets into the blob.
+ * The prefix of b is contained in the prefix of b+1 (a b-bit call loads only b bits per weight).
+ */
+ap_status ap_read_extent(int M, int K, int n, unsigned lut_mask, int b, size_t *slices_begin,
+                         size_t *slices_end, size_t *lut_begin, size_t *lut_end);
+
+/*
+ * Pack on the host and upload into caller-owned device memory.
+ *   dev_buf   device, dev_buf_bytes >= ap_packed_size(...), 256-byte aligned, must outlive the
+ *             handle; the library never allocates device memory for model data
+ *   stream    the upload is enqueued on it and has completed when the call returns
+ *   out       receives the handle (host object; release with ap_free)
+ * The host arrays may be released after return.
+ */
+ap_status ap_pack(const uint8_t *idx_host, int M, int K, int n, const uint16_t *const luts_host[9],
+                  void *dev_buf, size_t dev_buf_bytes, void *stream, ap_matrix **out);
+
+/* Adopt a blob that is already in device memory (e.g. a device-to-device copy of a packed
+ * matrix).  Reads the 256-byte header back to the host to validate it. */
+ap_status ap_attach(void *dev_buf, size_t dev_buf_bytes, void *stream, ap_matrix **out);
+
+/* Download the slices and undo the packing: writes M*K index bytes to idx_host_out (host).
+ * Synchronises `stream`. */
+ap_status ap_unpack(const ap_matrix *h, uint8_t *idx_host_out, void *stream);
+
+/*
+ * y[t][i] = sum_j  C_b[i][ idx[i][j] >> (n-b) ] * x[t][j],   0 <= t < batch     (Section 5.2)
+ *   h      packed matrix; b: 3 <= b <= n and a table for b was packed (else AP_ERR_BITS)
+ *   x_dev  device, batch*K binary16 row-major, 16-byte aligned
+ *   y_dev  device, batch*M binary16 row-major, 2-byte aligned; must not overlap x_dev or the blob
+ *   batch  1..8 (the paper switches to a dequantise + dense GEMM path above that, Section 6.2)
+ * Products are exact in binary32, accumulation is binary32, the result is rounded to binary16
+ * (round to nearest even).  Asynchronous on `stream`; allocates nothing, synchronises nothing,
+ * never repacks; the bit-width is chosen per call.  Results are deterministic (no atomics).
+ */
+ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int batch,
+                  void *stream);
+
+/* Shape and supported bit-widths of a handle; any output pointer may be NULL. */
+ap_status ap_matrix_info(const ap_matrix *h, int *M, int *K, int *n, unsigned *lut_mask);
+
+/* Releases the host handle only; the device buffer stays with the caller. NULL is allowed. */
+void ap_free(ap_matrix *h);
+
+/* Static, never NULL. */
+const char *ap_strerror(ap_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APGEMV_H */

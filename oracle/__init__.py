@@ -42,6 +42,8 @@ def lib():
         L.oracle_anyprecision_bytes.restype = ctypes.c_double
         L.oracle_anyprecision_bytes.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_uint,
                                                 ctypes.c_double]
+        L.oracle_num_threads.restype = ctypes.c_int
+        L.oracle_num_threads.argtypes = []
         _lib = L
     return _lib
 
@@ -52,6 +54,10 @@ def _u16(a):
         a = a.view(np.uint16)
     assert a.dtype == np.uint16
     return a
+
+
+def num_threads():
+    return lib().oracle_num_threads()
 
 
 def fp16_to_double(bits):

@@ -24,6 +24,19 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Threads the row loop of oracle_gemv will use (reported beside timings; no arithmetic here). */
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* IEEE 754 binary16 bit pattern -> double, exact (subnormals, signed zero, inf, nan). */
 double oracle_fp16_to_double(uint16_t h)

@@ -1,0 +1,149 @@
+// C-ABI entry points that touch the device: upload, download, attach, GEMV dispatch.
+#include <hip/hip_runtime_api.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+#include "pack.h"
+
+using namespace apgemv;
+
+struct ap_matrix {
+    uint32_t tag;
+    BlobHeader hdr;
+    uint8_t *dev;
+    int waves_per_group;
+};
+static constexpr uint32_t kHandleTag = 0x41504d58u;
+
+static bool handle_ok(const ap_matrix *h) { return h && h->tag == kHandleTag && h->dev; }
+
+static int env_waves()
+{
+    const char *e = std::getenv("APGEMV_WAVES");
+    return e ? std::atoi(e) : 0;
+}
+
+extern "C" ap_status ap_pack(const uint8_t *idx_host, int M, int K, int n,
+                             const uint16_t *const luts_host[9], void *dev_buf,
+                             size_t dev_buf_bytes, void *stream, ap_matrix **out)
+{
+    if (!idx_host || !luts_host || !dev_buf || !out) return AP_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(dev_buf) % AP_BLOB_ALIGN) return AP_ERR_INVALID_ARG;
+    ap_status s = check_shape(M, K, n);
+    if (s != AP_OK) return s;
+    unsigned mask = 0;
+    for (int b = AP_MIN_BITS; b <= n; ++b)
+        if (luts_host[b]) mask |= 1u << b;
+    BlobHeader hdr;
+    s = make_header(M, K, n, mask, &hdr);
+    if (s != AP_OK) return s;
+    if (dev_buf_bytes < hdr.total_bytes) return AP_ERR_BUFFER_TOO_SMALL;
+
+    std::vector<uint8_t> staging;
+    try {
+        staging.resize(hdr.total_bytes);
+    } catch (const std::bad_alloc &) {
+        return AP_ERR_INVALID_ARG;
+    }
+    s = ap_pack_host(idx_host, M, K, n, luts_host, staging.data(), staging.size());
+    if (s != AP_OK) return s;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(dev_buf, staging.data(), hdr.total_bytes, hipMemcpyHostToDevice, st) != hipSuccess)
+        return AP_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return AP_ERR_HIP;
+
+    ap_matrix *h = new (std::nothrow) ap_matrix;
+    if (!h) return AP_ERR_INVALID_ARG;
+    h->tag = kHandleTag;
+    h->hdr = hdr;
+    h->dev = static_cast<uint8_t *>(dev_buf);
+    h->waves_per_group = env_waves();
+    *out = h;
+    return AP_OK;
+}
+
+extern "C" ap_status ap_attach(void *dev_buf, size_t dev_buf_bytes, void *stream, ap_matrix **out)
+{
+    if (!dev_buf || !out || dev_buf_bytes < sizeof(BlobHeader)) return AP_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(dev_buf) % AP_BLOB_ALIGN) return AP_ERR_INVALID_ARG;
+    BlobHeader hdr;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(&hdr, dev_buf, sizeof(hdr), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return AP_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return AP_ERR_HIP;
+    ap_status s = validate_header(&hdr, dev_buf_bytes);
+    if (s != AP_OK) return s;
+    ap_matrix *h = new (std::nothrow) ap_matrix;
+    if (!h) return AP_ERR_INVALID_ARG;
+    h->tag = kHandleTag;
+    h->hdr = hdr;
+    h->dev = static_cast<uint8_t *>(dev_buf);
+    h->waves_per_group = env_waves();
+    *out = h;
+    return AP_OK;
+}
+
+extern "C" ap_status ap_unpack(const ap_matrix *h, uint8_t *idx_host_out, void *stream)
+{
+    if (!handle_ok(h) || !idx_host_out) return AP_ERR_INVALID_ARG;
+    const size_t bytes = h->hdr.slice_off + (size_t)h->hdr.n * h->hdr.slice_bytes;
+    std::vector<uint8_t> staging;
+    try {
+        staging.resize(bytes);
+    } catch (const std::bad_alloc &) {
+        return AP_ERR_INVALID_ARG;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(staging.data(), h->dev, bytes, hipMemcpyDeviceToHost, st) != hipSuccess)
+        return AP_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return AP_ERR_HIP;
+    BlobHeader hdr;
+    std::memcpy(&hdr, staging.data(), sizeof(hdr));
+    if (std::memcmp(&hdr, &h->hdr, sizeof(hdr)) != 0) return AP_ERR_INVALID_ARG;
+    unpack_slices(staging.data(), hdr, idx_host_out);
+    return AP_OK;
+}
+
+extern "C" ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int batch,
+                             void *stream)
+{
+    if (!handle_ok(h) || !x_dev || !y_dev) return AP_ERR_INVALID_ARG;
+    if (b < AP_MIN_BITS || b > h->hdr.n || !(h->hdr.lut_mask & (1u << b))) return AP_ERR_BITS;
+    if (batch < 1 || batch > AP_MAX_BATCH) return AP_ERR_BATCH;
+    if (reinterpret_cast<uintptr_t>(x_dev) % 16 || reinterpret_cast<uintptr_t>(y_dev) % 2)
+        return AP_ERR_INVALID_ARG;
+    GemvArgs a;
+    a.slices = h->dev + h->hdr.slice_off;
+    a.slice_bytes = h->hdr.slice_bytes;
+    a.lut = reinterpret_cast<const uint16_t *>(h->dev + h->hdr.lut_off[b]);
+    a.x = static_cast<const uint16_t *>(x_dev);
+    a.y = static_cast<uint16_t *>(y_dev);
+    a.M = h->hdr.M;
+    a.K = h->hdr.K;
+    a.b = b;
+    a.batch = batch;
+    a.waves_per_group = h->waves_per_group;
+    return launch_gemv(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+extern "C" ap_status ap_matrix_info(const ap_matrix *h, int *M, int *K, int *n, unsigned *lut_mask)
+{
+    if (!handle_ok(h)) return AP_ERR_INVALID_ARG;
+    if (M) *M = h->hdr.M;
+    if (K) *K = h->hdr.K;
+    if (n) *n = h->hdr.n;
+    if (lut_mask) *lut_mask = h->hdr.lut_mask;
+    return AP_OK;
+}
+
+extern "C" void ap_free(ap_matrix *h)
+{
+    if (!h) return;
+    h->tag = 0;
+    delete h;
+}

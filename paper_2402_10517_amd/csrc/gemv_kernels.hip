@@ -1,0 +1,256 @@
+// Any-precision GEMV kernels for gfx950 (CDNA4, wave64) and their launcher.
+//
+// Steps of one call (Any-Precision LLM, Section 5.2, the five thread-level operations): load the
+// first b bit slices of the lane's weights and the matching activations, turn the slices into
+// table indices, fetch centroids from the table rows staged in LDS, multiply-accumulate, reduce
+// over the lanes that share an output channel.  How each step is done differs from the paper's
+// kernel, which was written for 32-wide warps:
+//   * index formation needs no bit transpose: the slices are stored pre-rotated (layout.h), so a
+//     word of four table indices is (b-1) bit-selects with constant masks and one rotate;
+//   * b = 3 looks two weights up at once in a 64-entry table of centroid pairs and feeds the
+//     pair to one packed dot product (Section 5.3 "Merging Table Lookups");
+//   * a lane keeps its 32 activations in registers for 4 output rows;
+//   * the reduction over lanes uses DPP row operations, then LDS across the waves of the group.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include "kernels.h"
+#include "layout.h"
+
+namespace apgemv {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t rotl_c(uint32_t v, int r)
+{
+    r &= 31;
+    return r ? (v << r) | (v >> (32 - r)) : v;
+}
+// d = (m & a) | (~m & b): one v_bfi_b32
+__device__ __forceinline__ uint32_t bitsel(uint32_t m, uint32_t a, uint32_t b)
+{
+    return (m & a) | (~m & b);
+}
+__device__ __forceinline__ uint32_t rotr_v(uint32_t v, int r)
+{
+    return (r & 31) ? __builtin_amdgcn_alignbit(v, v, r & 31) : v;
+}
+__device__ __forceinline__ uint32_t comp(const uint4 &v, int i)
+{
+    return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
+}
+
+template <int B> struct Table {
+    static constexpr bool kPair = (B == 3);
+    // bytes of one row's table in LDS
+    static constexpr int kRowBytes = B == 3 ? 256 : B <= 6 ? 128 : B == 7 ? 256 : 512;
+    // LDS byte address of natural entry e (single-lookup modes): index bit of slice s at bit
+    // slice_rot(s); B = 8 uses all eight byte bits, so the byte is shifted left by one instead.
+    __device__ static constexpr uint32_t addr_mask()
+    {
+        uint32_t m = 0;
+        for (int s = 0; s < B; ++s) m |= 1u << slice_rot(s);
+        return m;
+    }
+    __device__ static uint32_t entry_addr(uint32_t e)
+    {
+        uint32_t a = 0;
+#pragma unroll
+        for (int s = 0; s < B; ++s) a |= ((e >> (B - 1 - s)) & 1u) << slice_rot(s);
+        return B == 8 ? a << 1 : a;
+    }
+};
+
+template <int ctrl, int row_mask> __device__ __forceinline__ float dpp_add(float v)
+{
+    int t = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, row_mask, 0xf, false);
+    return v + __builtin_bit_cast(float, t);
+}
+// Sum over the 64 lanes of a wave; the total ends up in lane 63.
+__device__ __forceinline__ float wave_sum_to_lane63(float v)
+{
+    v = dpp_add<0xB1, 0xf>(v);  // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E, 0xf>(v);  // quad_perm [2,3,0,1]
+    v = dpp_add<0x141, 0xf>(v); // row_half_mirror
+    v = dpp_add<0x140, 0xf>(v); // row_mirror: every lane of a row of 16 holds the row sum
+    v = dpp_add<0x142, 0xa>(v); // row_bcast15 into rows 1 and 3
+    v = dpp_add<0x143, 0xc>(v); // row_bcast31 into rows 2 and 3
+    return v;
+}
+
+template <int B, int NB>
+__global__ __launch_bounds__(256) void gemv_kernel(const uint8_t *__restrict__ slices,
+                                                    size_t slice_bytes,
+                                                    const uint16_t *__restrict__ lut,
+                                                    const uint16_t *__restrict__ x,
+                                                    uint16_t *__restrict__ y, int M, int K,
+                                                    int batch)
+{
+    using T = Table<B>;
+    constexpr int TB = T::kRowBytes;
+    __shared__ __attribute__((aligned(16))) uint8_t tab[kRowsPerGroup * TB];
+    __shared__ float red[4][kRowsPerGroup * NB];
+
+    const int g = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int nwaves = blockDim.x >> 6;
+    const int row0 = g * kRowsPerGroup;
+
+    // ---- stage the 4 rows' tables (Section 5.2: table rows live in the block's shared memory)
+    if constexpr (T::kPair) {
+        // 64 pair entries per row: index bits (i6 bit 2k) = code bit k of the even slot,
+        // (i6 bit 2k+1) = code bit k of the odd slot; entry = (C[even] , C[odd]) packed.
+        for (int i = threadIdx.x; i < kRowsPerGroup * 64; i += blockDim.x) {
+            const int r = i >> 6, i6 = i & 63;
+            const int row = row0 + r;
+            const int a = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
+            const int c = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
+            uint32_t v = 0;
+            if (row < M) v = (uint32_t)lut[(size_t)row * 8 + a] | ((uint32_t)lut[(size_t)row * 8 + c] << 16);
+            *reinterpret_cast<uint32_t *>(tab + r * TB + i6 * 4) = v;
+        }
+    } else {
+        constexpr int E = 1 << B;
+        for (int i = threadIdx.x; i < kRowsPerGroup * E; i += blockDim.x) {
+            const int r = i >> B, e = i & (E - 1);
+            const int row = row0 + r;
+            uint16_t v = 0;
+            if (row < M) v = lut[((size_t)row << B) + e];
+            *reinterpret_cast<uint16_t *>(tab + r * TB + T::entry_addr(e)) = v;
+        }
+    }
+    __syncthreads();
+
+    float acc[NB][kRowsPerGroup];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < kRowsPerGroup; ++r) acc[nb][r] = 0.f;
+
+    const int chunks = K / kChunkSlots;
+    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
+    for (int span = wave; span < nspans; span += nwaves) {
+        const int rem = chunks - span * kSpanLanes;
+        const int nl = rem < kSpanLanes ? rem : kSpanLanes;
+        if (lane < nl) {
+            const size_t unit = (size_t)g * chunks + (size_t)span * kSpanLanes + lane;
+            uint4 Q[B];
+#pragma unroll
+            for (int s = 0; s < B; ++s)
+                Q[s] = *reinterpret_cast<const uint4 *>(slices + (size_t)s * slice_bytes + unit * 16);
+            uint4 X[NB][4];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int xr = nb < batch ? nb : batch - 1;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    X[nb][t] = *reinterpret_cast<const uint4 *>(
+                        x + (size_t)xr * K + (size_t)span * kSpanCols + t * 8 * nl + lane * 8);
+            }
+#pragma unroll
+            for (int r = 0; r < kRowsPerGroup; ++r) {
+                const uint8_t *trow = tab + r * TB;
+                if constexpr (T::kPair) {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const int u = 2 * t;
+                        uint32_t v = bitsel(rotl_c(0x30303030u, u), comp(Q[1], r), comp(Q[2], r));
+                        v = bitsel(rotl_c(0xC0C0C0C0u, u), comp(Q[0], r), v);
+                        v = rotr_v(v, u);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const uint32_t a = (v >> (8 * j)) & 0xFCu;
+                            const uint32_t w = *reinterpret_cast<const uint32_t *>(trow + a);
+#pragma unroll
+                            for (int nb = 0; nb < NB; ++nb)
+                                acc[nb][r] = __builtin_amdgcn_fdot2(
+                                    __builtin_bit_cast(half2_t, w),
+                                    __builtin_bit_cast(half2_t, comp(X[nb][t], j)), acc[nb][r], false);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        uint32_t v = comp(Q[B - 1], r);
+#pragma unroll
+                        for (int s = B - 2; s >= 0; --s)
+                            v = bitsel(rotl_c(0x01010101u, u + slice_rot(s)), comp(Q[s], r), v);
+                        v = rotr_v(v, u);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const uint32_t byte = (v >> (8 * j)) & 0xFFu;
+                            const uint32_t a = B == 8 ? (byte << 1) : (byte & T::addr_mask());
+                            const _Float16 w = *reinterpret_cast<const _Float16 *>(trow + a);
+#pragma unroll
+                            for (int nb = 0; nb < NB; ++nb) {
+                                const half2_t xp = __builtin_bit_cast(half2_t, comp(X[nb][u >> 1], j));
+                                const _Float16 xv = (u & 1) ? xp.y : xp.x;
+                                acc[nb][r] = __builtin_fmaf((float)w, (float)xv, acc[nb][r]);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- reduce over lanes, then over the waves of the group (fixed order: deterministic)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < kRowsPerGroup; ++r) {
+            const float s = wave_sum_to_lane63(acc[nb][r]);
+            if (lane == 63) red[wave][nb * kRowsPerGroup + r] = s;
+        }
+    __syncthreads();
+    if (threadIdx.x < kRowsPerGroup * NB) {
+        const int nb = threadIdx.x / kRowsPerGroup, r = threadIdx.x % kRowsPerGroup;
+        float s = 0.f;
+        for (int w = 0; w < nwaves; ++w) s += red[w][threadIdx.x];
+        const int row = row0 + r;
+        if (row < M && nb < batch) {
+            const __half h = __float2half_rn(s);
+            y[(size_t)nb * M + row] = __builtin_bit_cast(uint16_t, h);
+        }
+    }
+}
+
+template <int B, int NB>
+static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
+{
+    const int groups = padded_rows(a.M) / kRowsPerGroup;
+    const int chunks = a.K / kChunkSlots;
+    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
+    int nw = a.waves_per_group;
+    if (nw <= 0) nw = nspans >= 4 ? 4 : nspans >= 2 ? 2 : 1;
+    if (nw > 4) nw = 4;
+    hipLaunchKernelGGL((gemv_kernel<B, NB>), dim3(groups), dim3(64 * nw), 0, stream, a.slices,
+                       a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
+    return hipGetLastError();
+}
+
+template <int B> static hipError_t launch_b(const GemvArgs &a, hipStream_t stream)
+{
+    if (a.batch == 1) return launch_one<B, 1>(a, stream);
+    if (a.batch == 2) return launch_one<B, 2>(a, stream);
+    if (a.batch <= 4) return launch_one<B, 4>(a, stream);
+    return launch_one<B, 8>(a, stream);
+}
+
+// Bit-width dispatch: one stored matrix, the kernel and the table are chosen per call
+// (Section 5.2: only the first b slices and the b-bit table are touched).
+hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream)
+{
+    switch (a.b) {
+    case 3: return launch_b<3>(a, stream);
+    case 4: return launch_b<4>(a, stream);
+    case 5: return launch_b<5>(a, stream);
+    case 6: return launch_b<6>(a, stream);
+    case 7: return launch_b<7>(a, stream);
+    case 8: return launch_b<8>(a, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+} // namespace apgemv

@@ -1,0 +1,24 @@
+// Internal interface between the C-ABI entry points and the HIP kernels.
+#ifndef APGEMV_KERNELS_H
+#define APGEMV_KERNELS_H
+
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace apgemv {
+
+struct GemvArgs {
+    const uint8_t *slices; // device: slice 0 of the packed matrix
+    size_t slice_bytes;
+    const uint16_t *lut;   // device: table of bit-width b, M * 2^b binary16
+    const uint16_t *x;     // device: batch * K binary16
+    uint16_t *y;           // device: batch * M binary16
+    int M, K, b, batch;
+    int waves_per_group;   // 0 = choose from the shape
+};
+
+hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream);
+
+} // namespace apgemv
+#endif

@@ -1,0 +1,171 @@
+"""Host-side checks of the C-ABI library: exports, packed format, error paths.  No GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2402_10517_amd import binding as B
+from paper_2402_10517_amd import inputs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ALL_BITS = list(range(3, 9))
+FULL_MASK = B.lut_mask(ALL_BITS)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "apgemv.h")).read()
+    declared = sorted(set(re.findall(r"\b(ap_[a-z_]+)\s*\(", header)))
+    assert set(declared) == set(B.EXPORTS)
+    raw = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(raw, name), name
+
+
+def test_strerror_is_static_text_for_every_status():
+    for s in range(0, 9):
+        assert isinstance(B.strerror(s), str) and B.strerror(s)
+
+
+def test_packed_size_is_n_bits_per_weight_plus_tables():
+    for (M, K) in [(512, 512), (4096, 4096), (11008, 4096), (4096, 11008), (37, 96)]:
+        size = B.ap_packed_size(M, K, 8, FULL_MASK)
+        Mp = (M + 3) // 4 * 4
+        exact = Mp * K + sum(M * 2 ** b * 2 for b in ALL_BITS)
+        assert exact <= size <= exact + 256 * 8            # header + per-region alignment only
+        small = B.ap_packed_size(M, K, 8, B.lut_mask([3, 4, 8]))
+        assert size - small >= M * (32 + 64 + 128) * 2     # only the supported tables are stored
+    # a 6-bit parent stores 6 bits per weight
+    assert B.ap_packed_size(4096, 4096, 6, B.lut_mask([3, 6])) < 4096 * 4096 * 6 // 8 + 4096 * 144 + 2048
+
+
+def test_read_extent_of_b_is_a_prefix_of_b_plus_one():
+    M, K = 4096, 11008
+    prev = None
+    for b in ALL_BITS:
+        s0, s1, l0, l1 = B.ap_read_extent(M, K, 8, FULL_MASK, b)
+        assert s1 - s0 == M * K * b // 8                    # exactly b bits per weight
+        assert l1 - l0 == M * 2 ** b * 2
+        if prev:
+            assert s0 == prev[0] and s1 > prev[1]
+            assert l0 >= prev[3]                            # tables do not overlap
+        assert l0 >= s0 + M * K                             # tables sit after all 8 slices
+        prev = (s0, s1, l0, l1)
+
+
+PATTERNS = ["random", "zeros", "ones", "single_bit", "walking", "ramp"]
+
+
+def _pattern(name, M, K, seed=0):
+    rng = np.random.default_rng(seed)
+    if name == "random":
+        return rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+    if name == "zeros":
+        return np.zeros((M, K), dtype=np.uint8)
+    if name == "ones":
+        return np.full((M, K), 255, dtype=np.uint8)
+    if name == "single_bit":
+        a = np.zeros((M, K), dtype=np.uint8)
+        a[rng.integers(0, M), rng.integers(0, K)] = 1 << int(rng.integers(0, 8))
+        return a
+    if name == "walking":
+        return (1 << ((np.arange(M)[:, None] + np.arange(K)[None, :]) % 8)).astype(np.uint8)
+    if name == "ramp":
+        return ((np.arange(M)[:, None] * 7 + np.arange(K)[None, :]) % 256).astype(np.uint8)
+    raise ValueError(name)
+
+
+def _luts(M, bits=ALL_BITS, seed=1):
+    rng = np.random.default_rng(seed)
+    return {b: rng.normal(0, 0.02, size=(M, 1 << b)).astype(np.float16) for b in bits}
+
+
+@pytest.mark.parametrize("pattern", PATTERNS)
+@pytest.mark.parametrize("M,K", [(4, 32), (5, 96), (64, 2048), (37, 2048 + 160), (130, 4096 + 32 * 63)])
+def test_host_pack_unpack_round_trip(M, K, pattern):
+    idx = _pattern(pattern, M, K, seed=M * 31 + K)
+    blob = B.ap_pack_host(idx, _luts(M))
+    assert np.array_equal(B.ap_unpack_host(blob, M, K), idx)
+
+
+@pytest.mark.parametrize("n", [3, 4, 6, 7])
+def test_round_trip_with_smaller_parent(n):
+    M, K = 19, 320
+    rng = np.random.default_rng(n)
+    idx = rng.integers(0, 1 << n, size=(M, K), dtype=np.uint8)
+    blob = B.ap_pack_host(idx, _luts(M, bits=range(3, n + 1)), n=n)
+    assert np.array_equal(B.ap_unpack_host(blob, M, K), idx)
+    bad = idx.copy()
+    bad[3, 5] = 1 << n
+    with pytest.raises(B.ApError) as e:
+        B.ap_pack_host(bad, _luts(M, bits=range(3, n + 1)), n=n)
+    assert e.value.status == 4
+
+
+def test_slice_isolation_flipping_bit_p_changes_only_slice_p():
+    M, K = 12, 2048 + 64
+    idx = _pattern("random", M, K, seed=5)
+    luts = _luts(M)
+    base = B.ap_pack_host(idx, luts)
+    slice_bytes = M * K // 8
+    for p in range(8):
+        mod = idx.copy()
+        mod[7, 1234] ^= 1 << p
+        blob = B.ap_pack_host(mod, luts)
+        diff = np.nonzero(blob != base)[0]
+        assert diff.size == 1                               # one bit of one byte
+        s = 7 - p                                           # slice 0 holds the most significant bit
+        assert 256 + s * slice_bytes <= diff[0] < 256 + (s + 1) * slice_bytes
+        assert bin(int(blob[diff[0]] ^ base[diff[0]])).count("1") == 1
+
+
+def test_tables_are_stored_verbatim():
+    M, K = 9, 64
+    idx = _pattern("random", M, K)
+    luts = _luts(M, bits=[3, 5, 8])
+    blob = B.ap_pack_host(idx, luts)
+    out = ctypes.c_uint16(0)
+    for b in (3, 5, 8):
+        for (i, e) in [(0, 0), (8, (1 << b) - 1), (4, 3)]:
+            st = B.lib.ap_blob_lut_entry(blob.ctypes.data, blob.size, b, i, e, ctypes.byref(out))
+            assert st == 0 and out.value == luts[b].view(np.uint16)[i, e]
+    assert B.lib.ap_blob_lut_entry(blob.ctypes.data, blob.size, 4, 0, 0, ctypes.byref(out)) == 3
+
+
+def test_error_paths_before_any_device_work():
+    sz = ctypes.c_size_t(0)
+    L = B.lib
+    assert L.ap_packed_size(0, 64, 8, FULL_MASK, ctypes.byref(sz)) == 2      # M < 1
+    assert L.ap_packed_size(8, 48, 8, FULL_MASK, ctypes.byref(sz)) == 2      # K % 32
+    assert L.ap_packed_size(8, 64, 9, FULL_MASK, ctypes.byref(sz)) == 3      # n
+    assert L.ap_packed_size(8, 64, 2, 1 << 2, ctypes.byref(sz)) == 3
+    assert L.ap_packed_size(8, 64, 6, B.lut_mask([3, 7]), ctypes.byref(sz)) == 3   # table above n
+    assert L.ap_packed_size(8, 64, 8, 0, ctypes.byref(sz)) == 3              # no table at all
+    assert L.ap_packed_size(8, 64, 8, FULL_MASK, None) == 1
+
+    M, K = 8, 64
+    idx = _pattern("random", M, K)
+    arr, keep = B._lut_array(_luts(M))
+    blob = np.empty(B.ap_packed_size(M, K, 8, FULL_MASK), dtype=np.uint8)
+    assert L.ap_pack_host(idx.ctypes.data, M, K, 8, arr, blob.ctypes.data, blob.size - 1) == 5
+    assert L.ap_pack_host(None, M, K, 8, arr, blob.ctypes.data, blob.size) == 1
+    assert L.ap_unpack_host(blob.ctypes.data, 10, idx.ctypes.data) == 1
+    junk = np.zeros(4096, dtype=np.uint8)
+    assert L.ap_unpack_host(junk.ctypes.data, junk.size, idx.ctypes.data) == 1    # bad magic
+
+    h = ctypes.c_void_p()
+    fake_dev = ctypes.c_void_p(0x10000)                                       # never dereferenced
+    assert L.ap_pack(None, M, K, 8, arr, fake_dev, 1 << 20, None, ctypes.byref(h)) == 1
+    assert L.ap_pack(idx.ctypes.data, M, 40, 8, arr, fake_dev, 1 << 20, None, ctypes.byref(h)) == 2
+    assert L.ap_pack(idx.ctypes.data, M, K, 8, arr, fake_dev, 16, None, ctypes.byref(h)) == 5
+    assert L.ap_pack(idx.ctypes.data, M, K, 8, arr, ctypes.c_void_p(0x10004), 1 << 20, None,
+                     ctypes.byref(h)) == 1                                    # misaligned buffer
+    assert L.ap_gemv(None, 4, fake_dev, fake_dev, 1, None) == 1
+    assert L.ap_unpack(None, idx.ctypes.data, None) == 1
+    assert L.ap_matrix_info(None, None, None, None, None) == 1
+    L.ap_free(None)
+
+
+def test_algorithmic_bytes_formula():
+    assert inputs.algorithmic_bytes(4096, 4096, 3) == 4096 * 4096 * 3 // 8 + 4096 * 16 + 8192 + 8192

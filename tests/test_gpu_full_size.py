@@ -1,0 +1,68 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times."""
+import numpy as np
+import pytest
+
+from paper_2402_10517_amd import inputs
+from gpu_util import check_against_oracle, run_gemv
+
+pytestmark = pytest.mark.gpu
+ALL_BITS = list(range(3, 9))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2402_10517_amd import binding
+    return binding
+
+
+@pytest.mark.parametrize("M,K", inputs.CONFIGS[2]["shapes"])
+def test_config2_llama7b_shapes_every_row(B, M, K):
+    idx, luts, x = inputs.make_case(2, M, K)
+    pm = B.ap_pack(idx, luts)
+    for b in ALL_BITS:
+        y = run_gemv(pm, b, x)
+        check_against_oracle(y, idx, luts[b], b, x)
+    assert np.array_equal(B.ap_unpack(pm), idx)
+    pm.close()
+
+
+@pytest.mark.parametrize("M,K", inputs.CONFIGS[3]["shapes"])
+def test_config3_llama13b_shapes_sampled_rows(B, M, K):
+    idx, luts, x = inputs.make_case(3, M, K)
+    pm = B.ap_pack(idx, luts)
+    rows = np.unique(np.concatenate([np.arange(0, 8), np.arange(M - 8, M),
+                                     np.random.default_rng(M).integers(0, M, size=512)]))
+    for b in ALL_BITS:
+        y = run_gemv(pm, b, x)
+        check_against_oracle(y, idx, luts[b], b, x, rows=rows)
+    pm.close()
+
+
+@pytest.mark.parametrize("M,K", inputs.CONFIGS[5]["shapes"])
+def test_config5_llama70b_shapes_small_batch_sampled_rows(B, M, K):
+    idx, luts, x = inputs.make_case(5, M, K, batch=8, sigma=0.01, bit_widths=[3, 5, 8])
+    pm = B.ap_pack(idx, luts)
+    rows = np.unique(np.concatenate([np.arange(0, 4), np.arange(M - 4, M),
+                                     np.random.default_rng(K).integers(0, M, size=256)]))
+    for b in (3, 5, 8):
+        for batch in (1, 2, 4, 8):
+            y = run_gemv(pm, b, x[:batch])
+            check_against_oracle(y, idx, luts[b], b, x[:batch], rows=rows)
+    pm.close()
+
+
+def test_config4_decode_step_bit_width_sequence(B):
+    """One decoder layer's seven matrices packed once; a seeded sequence of bit-widths is applied
+    without repacking and every output is checked on sampled rows."""
+    packed = []
+    for k, (M, K) in enumerate(inputs.DECODE_LAYER_SHAPES):
+        idx, luts, x = inputs.make_case(4, M, K, salt=k)
+        packed.append((idx, luts, x, B.ap_pack(idx, luts)))
+    seq = inputs.decode_bit_sequence(8)
+    for step, b in enumerate(seq):
+        for (idx, luts, x, pm) in packed:
+            rows = np.random.default_rng(step).integers(0, idx.shape[0], size=64)
+            y = run_gemv(pm, b, x)
+            check_against_oracle(y, idx, luts[b], b, x, rows=rows)
+    for p in packed:
+        p[3].close()

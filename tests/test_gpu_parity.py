@@ -1,0 +1,187 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU oracle on the same inputs."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from paper_2402_10517_amd import inputs
+from gpu_util import check_against_oracle, run_gemv
+
+pytestmark = pytest.mark.gpu
+ALL_BITS = list(range(3, 9))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2402_10517_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def tiny(B):
+    idx, luts, x = inputs.make_case(1, 512, 512)
+    pm = B.ap_pack(idx, luts)
+    yield idx, luts, x, pm
+    pm.close()
+
+
+@pytest.mark.parametrize("b", ALL_BITS)
+def test_config1_tiny_all_bit_widths(B, tiny, b):
+    idx, luts, x, pm = tiny
+    y = run_gemv(pm, b, x)
+    check_against_oracle(y, idx, luts[b], b, x)
+
+
+def test_device_round_trip_is_bit_exact(B, tiny):
+    idx, _, _, pm = tiny
+    assert np.array_equal(B.ap_unpack(pm), idx)
+    for (M, K) in [(37, 2048 + 160), (5, 96)]:
+        idx2, luts2, _ = inputs.make_case(11, M, K)
+        pm2 = B.ap_pack(idx2, luts2)
+        assert np.array_equal(B.ap_unpack(pm2), idx2)
+        pm2.close()
+
+
+# several spans per row, a ragged last span, rows not a multiple of 4, 1/2/4 waves per group
+RAGGED = [(37, 96), (4, 32), (70, 2048 + 160), (129, 4096 + 32), (66, 3 * 2048), (10, 5 * 2048 + 736),
+          (257, 9 * 2048 + 32)]
+
+
+@pytest.mark.parametrize("M,K", RAGGED)
+@pytest.mark.parametrize("b", ALL_BITS)
+def test_ragged_shapes(B, M, K, b):
+    idx, luts, x = inputs.make_case(12, M, K)
+    pm = B.ap_pack(idx, {b: luts[b]})
+    y = run_gemv(pm, b, x)
+    check_against_oracle(y, idx, luts[b], b, x)
+    pm.close()
+
+
+@pytest.mark.parametrize("batch", range(1, 9))
+@pytest.mark.parametrize("b", [3, 4, 6, 8])
+def test_batches_one_to_eight(B, batch, b):
+    M, K = 132, 2048 + 512
+    idx, luts, x = inputs.make_case(13, M, K, batch=batch, sigma=0.01)
+    pm = B.ap_pack(idx, {b: luts[b]})
+    y = run_gemv(pm, b, x)
+    assert y.shape == (batch, M)
+    check_against_oracle(y, idx, luts[b], b, x)
+    # a row of a batched call equals the batch-1 call on that row, bit for bit or within tolerance
+    y0 = run_gemv(pm, b, x[batch - 1:batch])
+    check_against_oracle(y0, idx, luts[b], b, x[batch - 1:batch])
+    pm.close()
+
+
+@pytest.mark.parametrize("b", ALL_BITS)
+def test_one_hot_activation_is_exact(B, b):
+    M, K = 64, 2048 + 96
+    idx, luts, _ = inputs.make_case(14, M, K)
+    pm = B.ap_pack(idx, {b: luts[b]})
+    for j in (0, 1, 7, 8, 511, 512, 1023, 2047, 2048, 2049, K - 33, K - 1):
+        x = np.zeros((1, K), dtype=np.float16)
+        x[0, j] = 1.0
+        y = run_gemv(pm, b, x)
+        expect = luts[b][np.arange(M), idx[:, j] >> (8 - b)]
+        assert np.array_equal(y[0].view(np.uint16) & 0x7fff != 0, expect.view(np.uint16) & 0x7fff != 0)
+        assert np.array_equal(y[0], expect), "column %d" % j
+    pm.close()
+
+
+@pytest.mark.parametrize("b", ALL_BITS)
+def test_integer_table_pins_bit_order_end_to_end(B, b):
+    M, K = 24, 2048 + 64
+    idx, _, _ = inputs.make_case(15, M, K)
+    lut = np.tile(np.arange(1 << b, dtype=np.float16), (M, 1))
+    pm = B.ap_pack(idx, {b: lut})
+    for j in (0, 5, 300, 2047, 2050, K - 1):
+        x = np.zeros((1, K), dtype=np.float16)
+        x[0, j] = 1.0
+        y = run_gemv(pm, b, x)
+        assert np.array_equal(y[0].astype(np.int64), idx[:, j].astype(np.int64) >> (8 - b))
+    # a short all-ones prefix keeps the exact integer sum below 2048, so binary16 holds it exactly
+    ncols = max(1, 2048 // (1 << b) // 2)
+    x = np.zeros((1, K), dtype=np.float16)
+    x[0, :ncols] = 1.0
+    y = run_gemv(pm, b, x)
+    assert np.array_equal(y[0].astype(np.int64), (idx[:, :ncols].astype(np.int64) >> (8 - b)).sum(axis=1))
+    pm.close()
+
+
+@pytest.mark.parametrize("b", ALL_BITS)
+def test_adversarial_tables(B, b):
+    M, K = 48, 2048 + 32
+    idx, luts, x = inputs.make_case(16, M, K)
+    rng = np.random.default_rng(b)
+    E = 1 << b
+    lut = luts[b].copy()
+    lut = lut[:, rng.permutation(E)]                      # unsorted
+    lut[0, :] = np.float16(6.0e-8)                        # subnormals
+    lut[1, ::2] = np.float16(-0.0)
+    lut[2, :] = np.float16(0.25)                          # all entries equal
+    lut[3, 0] = np.float16(65504.0)
+    lut[3, E - 1] = np.float16(-65504.0)
+    idx[5, :] = 0xA5                                      # a row whose indices are all equal
+    xs = (x.astype(np.float32) * 1e-3).astype(np.float16) # keeps 65504 * x finite
+    pm = B.ap_pack(idx, {b: lut})
+    for xv in (xs, np.zeros_like(x)):
+        y = run_gemv(pm, b, xv)
+        check_against_oracle(y, idx, lut, b, xv)
+    pm.close()
+
+
+def test_dispatch_sequence_without_repacking_and_determinism(B, tiny):
+    import torch
+    idx, luts, x, pm = tiny
+    before = pm.buf.clone()
+    fresh = {b: run_gemv(pm, b, x) for b in ALL_BITS}
+    rng = np.random.default_rng(4)
+    for b in rng.integers(3, 9, size=24).tolist():
+        y = run_gemv(pm, b, x)
+        assert np.array_equal(y.view(np.uint16), fresh[b].view(np.uint16))   # bit-identical repeats
+    assert torch.equal(before, pm.buf)                                         # blob untouched
+
+
+def test_output_canaries_and_sparse_support(B):
+    import torch
+    M, K = 100, 2048 + 64
+    idx, luts, x = inputs.make_case(17, M, K, batch=3)
+    pm = B.ap_pack(idx, {3: luts[3], 4: luts[4], 8: luts[8]})
+    guard = 64
+    ybuf = torch.full((guard + 3 * M + guard,), -7.0, dtype=torch.float16, device="cuda")
+    xd = torch.from_numpy(x).cuda()
+    sp = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    for b in (3, 4, 8):
+        st = B.lib.ap_gemv(pm.handle, b, xd.data_ptr(), ybuf.data_ptr() + 2 * guard, 3, sp)
+        assert st == 0
+        torch.cuda.synchronize()
+        out = ybuf.cpu().numpy()
+        assert np.all(out[:guard] == -7.0) and np.all(out[-guard:] == -7.0)
+        check_against_oracle(out[guard:-guard].reshape(3, M), idx, luts[b], b, x)
+    for b in (5, 6, 7, 2, 9):
+        assert B.lib.ap_gemv(pm.handle, b, xd.data_ptr(), ybuf.data_ptr(), 3, sp) == 3
+    assert B.lib.ap_gemv(pm.handle, 3, xd.data_ptr(), ybuf.data_ptr(), 0, sp) == 6
+    assert B.lib.ap_gemv(pm.handle, 3, xd.data_ptr(), ybuf.data_ptr(), 9, sp) == 6
+    assert B.lib.ap_gemv(pm.handle, 3, xd.data_ptr() + 2, ybuf.data_ptr(), 1, sp) == 1
+    pm.close()
+
+
+def test_smaller_parent_bit_width(B):
+    n, M, K = 6, 40, 2048 + 32
+    rng = np.random.default_rng(6)
+    idx = rng.integers(0, 1 << n, size=(M, K), dtype=np.uint8)
+    luts = {b: rng.normal(0, 0.02, size=(M, 1 << b)).astype(np.float16) for b in range(3, n + 1)}
+    x = rng.normal(0, 1, size=(2, K)).astype(np.float16)
+    pm = B.ap_pack(idx, luts, n=n)
+    for b in range(3, n + 1):
+        y = run_gemv(pm, b, x)
+        check_against_oracle(y, idx, luts[b], b, x, n=n)
+    pm.close()
+
+
+def test_attach_to_a_device_copy(B, tiny):
+    idx, luts, x, pm = tiny
+    pm2 = pm.clone()
+    assert pm2.buf.data_ptr() != pm.buf.data_ptr()
+    for b in (3, 8):
+        assert np.array_equal(run_gemv(pm2, b, x).view(np.uint16), run_gemv(pm, b, x).view(np.uint16))
+    pm2.close()
