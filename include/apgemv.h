@@ -66,7 +66,8 @@ ap_status ap_pack_host(const uint8_t *idx, int M, int K, int n, const uint16_t *
  * (host).  Bit-exact round trip is part of the contract. */
 ap_status ap_unpack_host(const void *blob, size_t blob_bytes, uint8_t *idx_out);
 
-/* Reads table entry e of row i for bit-width b back out of a packed blob (host): binary16 bits. */
+/* Reads table entry e (natural index) of row i for bit-width b back out of a packed blob (host):
+ * binary16 bits.  Inside the blob the entries of a row are stored in the kernel's lookup order. */
 ap_status ap_blob_lut_entry(const void *blob, size_t blob_bytes, int b, int row, int entry,
                             uint16_t *out);
 

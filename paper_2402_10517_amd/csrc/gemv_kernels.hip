@@ -26,38 +26,36 @@ __device__ __forceinline__ uint32_t rotl_c(uint32_t v, int r)
     r &= 31;
     return r ? (v << r) | (v >> (32 - r)) : v;
 }
-// d = (m & a) | (~m & b): one v_bfi_b32
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// d = (m & a) | (~m & b) with a constant mask: one v_bfi_b32 (the mask sits in an SGPR)
 __device__ __forceinline__ uint32_t bitsel(uint32_t m, uint32_t a, uint32_t b)
 {
-    return (m & a) | (~m & b);
+    uint32_t d;
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(d) : "s"(m), "v"(a), "v"(b));
+    return d;
 }
 __device__ __forceinline__ uint32_t rotr_v(uint32_t v, int r)
 {
     return (r & 31) ? __builtin_amdgcn_alignbit(v, v, r & 31) : v;
-}
-__device__ __forceinline__ uint32_t comp(const uint4 &v, int i)
-{
-    return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
 }
 
 template <int B> struct Table {
     static constexpr bool kPair = (B == 3);
     // bytes of one row's table in LDS
     static constexpr int kRowBytes = B == 3 ? 256 : B <= 6 ? 128 : B == 7 ? 256 : 512;
-    // LDS byte address of natural entry e (single-lookup modes): index bit of slice s at bit
-    // slice_rot(s); B = 8 uses all eight byte bits, so the byte is shifted left by one instead.
+    // Single-lookup modes: the LDS byte address of an index is the merged byte masked to the
+    // positions slice_rot(0..B-1); B = 8 uses all eight byte bits and shifts left by one instead.
     __device__ static constexpr uint32_t addr_mask()
     {
         uint32_t m = 0;
         for (int s = 0; s < B; ++s) m |= 1u << slice_rot(s);
         return m;
     }
-    __device__ static uint32_t entry_addr(uint32_t e)
+    // LDS byte address of the entry stored at position c of a row (lut_stored_pos order).
+    __device__ static constexpr uint32_t stored_addr(uint32_t c)
     {
-        uint32_t a = 0;
-#pragma unroll
-        for (int s = 0; s < B; ++s) a |= ((e >> (B - 1 - s)) & 1u) << slice_rot(s);
-        return B == 8 ? a << 1 : a;
+        return B == 4 ? (((c & 8u) << 3) | ((c & 7u) << 2)) : B == 5 ? (c << 2) : (c << 1);
     }
 };
 
@@ -78,49 +76,161 @@ __device__ __forceinline__ float wave_sum_to_lane63(float v)
     return v;
 }
 
+// Copy the 4 rows' tables of this group from global memory into their LDS image.
+template <int B>
+__device__ __forceinline__ void stage_tables(uint8_t *tab, uint16_t *nat, const uint16_t *__restrict__ lut,
+                                             int row0, int M)
+{
+    using T = Table<B>;
+    constexpr int TB = T::kRowBytes;
+    const int tid = threadIdx.x, nth = blockDim.x;
+    if constexpr (B == 3) {
+        // natural 8-entry rows first, then the 64-entry table of centroid pairs: pair index bit 2k
+        // is code bit k of the even slot, bit 2k+1 is code bit k of the odd slot.
+        if (tid < kRowsPerGroup * 4) {
+            const int r = tid >> 2;
+            uint32_t v = 0;
+            if (row0 + r < M) v = reinterpret_cast<const uint32_t *>(lut + (size_t)row0 * 8)[tid];
+            reinterpret_cast<uint32_t *>(nat)[tid] = v;
+        }
+        __syncthreads();
+        for (int i = tid; i < kRowsPerGroup * 64; i += nth) {
+            const int r = i >> 6, i6 = i & 63;
+            const int a = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
+            const int c = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
+            const uint32_t v = (uint32_t)nat[r * 8 + a] | ((uint32_t)nat[r * 8 + c] << 16);
+            *reinterpret_cast<uint32_t *>(tab + r * TB + i6 * 4) = v;
+        }
+    } else if constexpr (B >= 6) {
+        // stored order = LDS order, rows contiguous: straight 16-byte copies
+        constexpr int kChunks = kRowsPerGroup * TB / 16;
+        const uint4 *src = reinterpret_cast<const uint4 *>(lut + ((size_t)row0 << B));
+        for (int i = tid; i < kChunks; i += nth) {
+            const int r = i / (TB / 16);
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (row0 + r < M) v = src[i];
+            reinterpret_cast<uint4 *>(tab)[i] = v;
+        }
+    } else {
+        // B = 4, 5: two stored entries per dword, spread to their dword-strided LDS addresses
+        constexpr int kDwordsPerRow = (1 << B) / 2;
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(lut + ((size_t)row0 << B));
+        for (int i = tid; i < kRowsPerGroup * kDwordsPerRow; i += nth) {
+            const int r = i / kDwordsPerRow, k = i % kDwordsPerRow;
+            uint32_t v = 0;
+            if (row0 + r < M) v = src[i];
+            uint8_t *dst = tab + r * TB + T::stored_addr(2 * k);
+            *reinterpret_cast<uint16_t *>(dst) = (uint16_t)v;
+            *reinterpret_cast<uint16_t *>(dst + 4) = (uint16_t)(v >> 16);
+        }
+    }
+}
+
+// Index formation, table lookup and multiply-accumulate for the lane's 32 slots of 4 rows
+// (Section 5.2 steps 2-5).
 template <int B, int NB>
-__global__ __launch_bounds__(256) void gemv_kernel(const uint8_t *__restrict__ slices,
-                                                    size_t slice_bytes,
-                                                    const uint16_t *__restrict__ lut,
-                                                    const uint16_t *__restrict__ x,
-                                                    uint16_t *__restrict__ y, int M, int K,
-                                                    int batch)
+__device__ __forceinline__ void compute_unit(const u32x4 (&Q)[B], const u32x4 (&X)[NB][4],
+                                             const uint8_t *tab, float (&acc)[NB][kRowsPerGroup])
+{
+    using T = Table<B>;
+    constexpr int TB = T::kRowBytes;
+#pragma unroll
+    for (int r = 0; r < kRowsPerGroup; ++r) {
+        const uint8_t *trow = tab + r * TB;
+        if constexpr (T::kPair) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int u = 2 * t;
+                uint32_t v = bitsel(rotl_c(0x30303030u, u), Q[1][r], Q[2][r]);
+                v = bitsel(rotl_c(0xC0C0C0C0u, u), Q[0][r], v);
+                v = rotr_v(v, u);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t a = (v >> (8 * j)) & 0xFCu;
+                    const uint32_t w = *reinterpret_cast<const uint32_t *>(trow + a);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        // (copy the vector element first: a bit cast applied directly to a vector
+                        // element reads element 0)
+                        const uint32_t xw = X[nb][t][j];
+                        acc[nb][r] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w),
+                                                            __builtin_bit_cast(half2_t, xw), acc[nb][r], false);
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                uint32_t v = Q[B - 1][r];
+#pragma unroll
+                for (int s = B - 2; s >= 0; --s)
+                    v = bitsel(rotl_c(0x01010101u, u + slice_rot(s)), Q[s][r], v);
+                v = rotr_v(v, u);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t byte = (v >> (8 * j)) & 0xFFu;
+                    const uint32_t a = B == 8 ? (byte << 1) : (byte & T::addr_mask());
+                    const _Float16 w = *reinterpret_cast<const _Float16 *>(trow + a);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const uint32_t xw = X[nb][u >> 1][j];
+                        const half2_t xp = __builtin_bit_cast(half2_t, xw);
+                        const _Float16 xv = (u & 1) ? xp.y : xp.x;
+                        acc[nb][r] = __builtin_fmaf((float)w, (float)xv, acc[nb][r]);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// One workgroup per group of 4 rows.  LOOP = false: one wave per span of 2048 columns (the
+// launcher guarantees blockDim = 64 * nspans); the wave's loads go out before the tables are
+// staged, so both latencies overlap.  LOOP = true: waves stride over the spans.
+template <int B, int NB, bool LOOP, int MAXT>
+__global__ __launch_bounds__(MAXT) void gemv_kernel(const uint8_t *__restrict__ slices,
+                                                     size_t slice_bytes,
+                                                     const uint16_t *__restrict__ lut,
+                                                     const uint16_t *__restrict__ x,
+                                                     uint16_t *__restrict__ y, int M, int K,
+                                                     int batch)
 {
     using T = Table<B>;
     constexpr int TB = T::kRowBytes;
     __shared__ __attribute__((aligned(16))) uint8_t tab[kRowsPerGroup * TB];
-    __shared__ float red[4][kRowsPerGroup * NB];
+    __shared__ __attribute__((aligned(16))) uint16_t nat[kRowsPerGroup * 8];
+    __shared__ float red[MAXT / 64][kRowsPerGroup * NB];
 
     const int g = blockIdx.x;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int nwaves = blockDim.x >> 6;
     const int row0 = g * kRowsPerGroup;
+    const int chunks = K / kChunkSlots;
+    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
 
-    // ---- stage the 4 rows' tables (Section 5.2: table rows live in the block's shared memory)
-    if constexpr (T::kPair) {
-        // 64 pair entries per row: index bits (i6 bit 2k) = code bit k of the even slot,
-        // (i6 bit 2k+1) = code bit k of the odd slot; entry = (C[even] , C[odd]) packed.
-        for (int i = threadIdx.x; i < kRowsPerGroup * 64; i += blockDim.x) {
-            const int r = i >> 6, i6 = i & 63;
-            const int row = row0 + r;
-            const int a = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
-            const int c = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
-            uint32_t v = 0;
-            if (row < M) v = (uint32_t)lut[(size_t)row * 8 + a] | ((uint32_t)lut[(size_t)row * 8 + c] << 16);
-            *reinterpret_cast<uint32_t *>(tab + r * TB + i6 * 4) = v;
+    u32x4 Q[B];
+    u32x4 X[NB][4];
+    // Loads of the lane's slice words and activations for one span (Section 5.2 step 1).
+    auto issue_loads = [&](int span, int nl) {
+        const size_t unit = (size_t)g * chunks + (size_t)span * kSpanLanes + lane;
+#pragma unroll
+        for (int s = 0; s < B; ++s)
+            Q[s] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4 *>(slices + (size_t)s * slice_bytes + unit * 16));
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int xr = nb < batch ? nb : batch - 1;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                X[nb][t] = *reinterpret_cast<const u32x4 *>(x + (size_t)xr * K + (size_t)span * kSpanCols +
+                                                            t * 8 * nl + lane * 8);
         }
-    } else {
-        constexpr int E = 1 << B;
-        for (int i = threadIdx.x; i < kRowsPerGroup * E; i += blockDim.x) {
-            const int r = i >> B, e = i & (E - 1);
-            const int row = row0 + r;
-            uint16_t v = 0;
-            if (row < M) v = lut[((size_t)row << B) + e];
-            *reinterpret_cast<uint16_t *>(tab + r * TB + T::entry_addr(e)) = v;
-        }
-    }
-    __syncthreads();
+    };
+    auto lanes_of = [&](int span) {
+        const int rem = chunks - span * kSpanLanes;
+        return rem < kSpanLanes ? rem : kSpanLanes;
+    };
 
     float acc[NB][kRowsPerGroup];
 #pragma unroll
@@ -128,69 +238,21 @@ __global__ __launch_bounds__(256) void gemv_kernel(const uint8_t *__restrict__ s
 #pragma unroll
         for (int r = 0; r < kRowsPerGroup; ++r) acc[nb][r] = 0.f;
 
-    const int chunks = K / kChunkSlots;
-    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
-    for (int span = wave; span < nspans; span += nwaves) {
-        const int rem = chunks - span * kSpanLanes;
-        const int nl = rem < kSpanLanes ? rem : kSpanLanes;
-        if (lane < nl) {
-            const size_t unit = (size_t)g * chunks + (size_t)span * kSpanLanes + lane;
-            uint4 Q[B];
-#pragma unroll
-            for (int s = 0; s < B; ++s)
-                Q[s] = *reinterpret_cast<const uint4 *>(slices + (size_t)s * slice_bytes + unit * 16);
-            uint4 X[NB][4];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int xr = nb < batch ? nb : batch - 1;
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    X[nb][t] = *reinterpret_cast<const uint4 *>(
-                        x + (size_t)xr * K + (size_t)span * kSpanCols + t * 8 * nl + lane * 8);
-            }
-#pragma unroll
-            for (int r = 0; r < kRowsPerGroup; ++r) {
-                const uint8_t *trow = tab + r * TB;
-                if constexpr (T::kPair) {
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const int u = 2 * t;
-                        uint32_t v = bitsel(rotl_c(0x30303030u, u), comp(Q[1], r), comp(Q[2], r));
-                        v = bitsel(rotl_c(0xC0C0C0C0u, u), comp(Q[0], r), v);
-                        v = rotr_v(v, u);
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const uint32_t a = (v >> (8 * j)) & 0xFCu;
-                            const uint32_t w = *reinterpret_cast<const uint32_t *>(trow + a);
-#pragma unroll
-                            for (int nb = 0; nb < NB; ++nb)
-                                acc[nb][r] = __builtin_amdgcn_fdot2(
-                                    __builtin_bit_cast(half2_t, w),
-                                    __builtin_bit_cast(half2_t, comp(X[nb][t], j)), acc[nb][r], false);
-                        }
-                    }
-                } else {
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        uint32_t v = comp(Q[B - 1], r);
-#pragma unroll
-                        for (int s = B - 2; s >= 0; --s)
-                            v = bitsel(rotl_c(0x01010101u, u + slice_rot(s)), comp(Q[s], r), v);
-                        v = rotr_v(v, u);
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const uint32_t byte = (v >> (8 * j)) & 0xFFu;
-                            const uint32_t a = B == 8 ? (byte << 1) : (byte & T::addr_mask());
-                            const _Float16 w = *reinterpret_cast<const _Float16 *>(trow + a);
-#pragma unroll
-                            for (int nb = 0; nb < NB; ++nb) {
-                                const half2_t xp = __builtin_bit_cast(half2_t, comp(X[nb][u >> 1], j));
-                                const _Float16 xv = (u & 1) ? xp.y : xp.x;
-                                acc[nb][r] = __builtin_fmaf((float)w, (float)xv, acc[nb][r]);
-                            }
-                        }
-                    }
-                }
+    if constexpr (!LOOP) {
+        const int nl = lanes_of(wave);
+        const bool active = lane < nl;
+        if (active) issue_loads(wave, nl);
+        stage_tables<B>(tab, nat, lut, row0, M);
+        __syncthreads();
+        if (active) compute_unit<B, NB>(Q, X, tab, acc);
+    } else {
+        stage_tables<B>(tab, nat, lut, row0, M);
+        __syncthreads();
+        for (int span = wave; span < nspans; span += nwaves) {
+            const int nl = lanes_of(span);
+            if (lane < nl) {
+                issue_loads(span, nl);
+                compute_unit<B, NB>(Q, X, tab, acc);
             }
         }
     }
@@ -219,14 +281,22 @@ __global__ __launch_bounds__(256) void gemv_kernel(const uint8_t *__restrict__ s
 template <int B, int NB>
 static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
 {
+    // batch 1 and 2 fit 128 registers per lane, so a group may have up to 16 waves;
+    // batch 4 and 8 keep 4 or 8 activation rows in registers and are capped at 4 waves.
+    constexpr int kMaxWaves = NB <= 2 ? 16 : 4;
+    constexpr int kMaxThreads = 64 * kMaxWaves;
     const int groups = padded_rows(a.M) / kRowsPerGroup;
     const int chunks = a.K / kChunkSlots;
     const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
-    int nw = a.waves_per_group;
-    if (nw <= 0) nw = nspans >= 4 ? 4 : nspans >= 2 ? 2 : 1;
-    if (nw > 4) nw = 4;
-    hipLaunchKernelGGL((gemv_kernel<B, NB>), dim3(groups), dim3(64 * nw), 0, stream, a.slices,
-                       a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
+    int cap = kMaxWaves;
+    if (a.waves_per_group > 0 && a.waves_per_group < cap) cap = a.waves_per_group;
+    if (nspans <= cap) {
+        hipLaunchKernelGGL((gemv_kernel<B, NB, false, kMaxThreads>), dim3(groups), dim3(64 * nspans), 0,
+                           stream, a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
+    } else {
+        hipLaunchKernelGGL((gemv_kernel<B, NB, true, kMaxThreads>), dim3(groups), dim3(64 * cap), 0,
+                           stream, a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
+    }
     return hipGetLastError();
 }
 

@@ -37,7 +37,7 @@ constexpr int kChunkSlots = 32;
 constexpr int kSpanLanes = 64;
 constexpr int kSpanCols = kSpanLanes * kChunkSlots; // 2048
 constexpr uint32_t kMagic = 0x31475041u;            // "APG1"
-constexpr uint32_t kLayoutVersion = 1;
+constexpr uint32_t kLayoutVersion = 2;
 constexpr size_t kAlign = 256;
 
 // Rotation of slice s (s = 0 is the most significant index bit).  For a b-bit call the used
@@ -52,6 +52,26 @@ APGEMV_HD constexpr int slice_rot(int s)
 {
     constexpr int rot[8] = {6, 4, 2, 3, 5, 1, 7, 0};
     return rot[s];
+}
+
+// Centroid tables are stored per row in the order of the kernel's LDS addressing, so staging is a
+// plain copy.  For bit-widths that look up one weight at a time (b >= 4) the table address of an
+// index is built from the index bits sitting at byte positions slice_rot(0..b-1); sorting those
+// positions ascending and numbering them 0..b-1 gives the stored position of an entry:
+// stored position = sum over slices s < b of (index bit of slice s) << rank_b(slice_rot(s)).
+// b = 3 (pair lookups) keeps the natural order.  Natural entry e has the bit of slice s at
+// bit (b-1-s).
+APGEMV_HD constexpr int lut_stored_pos(int b, int e)
+{
+    if (b <= 3) return e;
+    int pos = 0;
+    for (int s = 0; s < b; ++s) {
+        int rank = 0;
+        for (int s2 = 0; s2 < b; ++s2)
+            if (slice_rot(s2) < slice_rot(s)) ++rank;
+        pos |= ((e >> (b - 1 - s)) & 1) << rank;
+    }
+    return pos;
 }
 
 struct BlobHeader { // first 256 bytes of the blob, little endian

@@ -186,8 +186,15 @@ extern "C" ap_status ap_pack_host(const uint8_t *idx, int M, int K, int n,
     std::memset(out, 0, h.total_bytes);
     std::memcpy(out, &h, sizeof(h));
     pack_slices(idx, h, out);
-    for (int b = AP_MIN_BITS; b <= n; ++b)
-        if (luts[b]) std::memcpy(out + h.lut_off[b], luts[b], (size_t)M * ((size_t)2 << b));
+    for (int b = AP_MIN_BITS; b <= n; ++b) {
+        if (!luts[b]) continue;
+        const int E = 1 << b;
+        std::vector<int> pos(E);
+        for (int e = 0; e < E; ++e) pos[e] = lut_stored_pos(b, e);
+        uint16_t *dst = reinterpret_cast<uint16_t *>(out + h.lut_off[b]);
+        for (int i = 0; i < M; ++i)
+            for (int e = 0; e < E; ++e) dst[(size_t)i * E + pos[e]] = luts[b][(size_t)i * E + e];
+    }
     return AP_OK;
 }
 
@@ -213,7 +220,7 @@ extern "C" ap_status ap_blob_lut_entry(const void *blob, size_t blob_bytes, int 
     if (b < AP_MIN_BITS || b > h.n || !(h.lut_mask & (1u << b))) return AP_ERR_BITS;
     if (row < 0 || row >= h.M || entry < 0 || entry >= (1 << b)) return AP_ERR_INVALID_ARG;
     std::memcpy(out, static_cast<const uint8_t *>(blob) + h.lut_off[b] +
-                         ((size_t)row << (b + 1)) + (size_t)entry * 2, 2);
+                         ((size_t)row << (b + 1)) + (size_t)lut_stored_pos(b, entry) * 2, 2);
     return AP_OK;
 }
 

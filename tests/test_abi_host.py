@@ -120,16 +120,21 @@ def test_slice_isolation_flipping_bit_p_changes_only_slice_p():
         assert bin(int(blob[diff[0]] ^ base[diff[0]])).count("1") == 1
 
 
-def test_tables_are_stored_verbatim():
+def test_tables_read_back_entry_by_entry():
     M, K = 9, 64
     idx = _pattern("random", M, K)
     luts = _luts(M, bits=[3, 5, 8])
     blob = B.ap_pack_host(idx, luts)
     out = ctypes.c_uint16(0)
     for b in (3, 5, 8):
-        for (i, e) in [(0, 0), (8, (1 << b) - 1), (4, 3)]:
-            st = B.lib.ap_blob_lut_entry(blob.ctypes.data, blob.size, b, i, e, ctypes.byref(out))
-            assert st == 0 and out.value == luts[b].view(np.uint16)[i, e]
+        for i in range(M):
+            for e in range(1 << b):
+                st = B.lib.ap_blob_lut_entry(blob.ctypes.data, blob.size, b, i, e, ctypes.byref(out))
+                assert st == 0 and out.value == luts[b].view(np.uint16)[i, e]
+        # the stored row is a permutation of the given row
+        _, _, l0, l1 = B.ap_read_extent(M, K, 8, B.lut_mask([3, 5, 8]), b)
+        stored = blob[l0:l1].view(np.uint16).reshape(M, 1 << b)
+        assert np.array_equal(np.sort(stored, axis=1), np.sort(luts[b].view(np.uint16), axis=1))
     assert B.lib.ap_blob_lut_entry(blob.ctypes.data, blob.size, 4, 0, 0, ctypes.byref(out)) == 3
 
 
