@@ -34,6 +34,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying HIP graphs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--detail", action="store_true", help="also print a per-(shape, b) table to stderr")
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 5],
+                    help="benchmark configuration to run (default 2 = the headline workload)")
+    ap.add_argument("--batch", type=int, default=1, help="batch size (exploration only; headline is 1)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -50,17 +53,20 @@ def main():
         sys.exit(3)
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    shapes = inputs.CONFIGS[2]["shapes"]
+    cfg = inputs.CONFIGS[args.config]
+    shapes = cfg["shapes"]
+    batch = args.batch
     bits = list(range(3, 9))
 
     # ---- inputs resident in HBM -------------------------------------------------------------
     cases = []
     for (M, K) in shapes:
-        idx, luts, x = inputs.make_case(2, M, K)
+        idx, luts, x = inputs.make_case(args.config, M, K, batch=batch, sigma=cfg["sigma"])
         pm = B.ap_pack(idx, luts, device=dev)
-        copies = [pm] + [pm.clone() for _ in range(COPIES - 1)]
+        ncopies = max(2, min(COPIES, int(2.5e9 // pm.buf.numel())))
+        copies = [pm] + [pm.clone() for _ in range(ncopies - 1)]
         xd = torch.from_numpy(x).to(dev)
-        yd = torch.empty((1, M), dtype=torch.float16, device=dev)
+        yd = torch.empty((batch, M), dtype=torch.float16, device=dev)
         cases.append(dict(M=M, K=K, idx=idx, luts=luts, x=x, copies=copies, xd=xd, yd=yd))
     stream = torch.cuda.current_stream()
     sp = ctypes.c_void_p(stream.cuda_stream)
@@ -70,13 +76,13 @@ def main():
         c = phase * len(bits)
         for b in bits:
             for cs in cases:
-                pm = cs["copies"][c % COPIES]
-                st = B.lib.ap_gemv(pm.handle, b, cs["xd"].data_ptr(), cs["yd"].data_ptr(), 1, sp)
+                pm = cs["copies"][c % len(cs["copies"])]
+                st = B.lib.ap_gemv(pm.handle, b, cs["xd"].data_ptr(), cs["yd"].data_ptr(), batch, sp)
                 if st != 0:
                     raise RuntimeError("ap_gemv failed: %s" % B.strerror(st))
             c += 1
 
-    step_bytes = sum(inputs.algorithmic_bytes(cs["M"], cs["K"], b) for cs in cases for b in bits)
+    step_bytes = sum(inputs.algorithmic_bytes(cs["M"], cs["K"], b, batch) for cs in cases for b in bits)
 
     graphs = None
     if not args.no_graph:
@@ -124,17 +130,18 @@ def main():
     reps = 5 * COPIES
     for b in bits:
         for cs in cases:
-            for r in range(COPIES):
-                B.lib.ap_gemv(cs["copies"][r].handle, b, cs["xd"].data_ptr(), cs["yd"].data_ptr(), 1, sp)
+            nc = len(cs["copies"])
+            for r in range(nc):
+                B.lib.ap_gemv(cs["copies"][r].handle, b, cs["xd"].data_ptr(), cs["yd"].data_ptr(), batch, sp)
             torch.cuda.synchronize()
             a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a0.record()
             for r in range(reps):
-                B.lib.ap_gemv(cs["copies"][r % COPIES].handle, b, cs["xd"].data_ptr(), cs["yd"].data_ptr(), 1, sp)
+                B.lib.ap_gemv(cs["copies"][r % nc].handle, b, cs["xd"].data_ptr(), cs["yd"].data_ptr(), batch, sp)
             a1.record()
             torch.cuda.synchronize()
             us = a0.elapsed_time(a1) * 1e3 / reps
-            nbytes = inputs.algorithmic_bytes(cs["M"], cs["K"], b)
+            nbytes = inputs.algorithmic_bytes(cs["M"], cs["K"], b, batch)
             per_call.append(dict(M=cs["M"], K=cs["K"], b=b, us=round(us, 3), bytes=nbytes,
                                  GBps=round(nbytes / us / 1e3, 1),
                                  frac_of_peak=round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)))
@@ -148,7 +155,7 @@ def main():
     dom_b = max(by_b, key=lambda k: by_b[k]["us"])
     dom = by_b[dom_b]
     achieved = dom["bytes"] / dom["us"] / 1e3
-    roofline = dict(bound="hbm", kernel="gemv_kernel<%d,1>" % dom_b, achieved=round(achieved, 1),
+    roofline = dict(bound="hbm", kernel="gemv_kernel<%d,%d>" % (dom_b, batch), achieved=round(achieved, 1),
                     peak=HBM_PEAK_GBPS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBPS, 4),
                     bytes_per_launch=dom["bytes"] // dom["n"],
                     avg_launch_us=round(dom["us"] / dom["n"], 3), traffic=None)
@@ -176,11 +183,13 @@ def main():
                unit="GB/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=round(ms_per_step, 5), higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="f16 tables and activations, f32 accumulate", data="synthetic",
-               config=dict(workload="configs[1]: Llama-2-7B linears 4096x4096, 11008x4096, 4096x11008; "
-                                    "8-bit parent, b=3..8, batch 1; one step = 18 ap_gemv calls",
+               config=dict(workload=("configs[1]: Llama-2-7B linears 4096x4096, 11008x4096, 4096x11008; "
+                                     "8-bit parent, b=3..8, batch 1; one step = 18 ap_gemv calls")
+                           if args.config == 2 and batch == 1 else
+                           "exploration: config %d (%s) shapes %s, batch %d" % (args.config, cfg["name"], shapes, batch),
                            calls_per_step=len(bits) * len(cases), bytes_per_step=step_bytes,
                            device_copies=COPIES, launch="hip-graph" if graphs is not None else "python-loop"),
-               frac_of_hbm_peak=round(value / HBM_PEAK_GBPS, 4), us_per_call=round(ms_per_step * 1e3 / 18, 3),
+               frac_of_hbm_peak=round(value / HBM_PEAK_GBPS, 4), us_per_call=round(ms_per_step * 1e3 / (len(bits) * len(cases)), 3),
                wall_ms=round(wall_ms, 2), roofline=roofline, cpu_baseline=cpu, per_call=per_call)
     if args.detail:
         for pc in per_call:

@@ -184,10 +184,11 @@ __device__ __forceinline__ void compute_unit(const u32x4 (&Q)[B], const u32x4 (&
     }
 }
 
-// One workgroup per group of 4 rows.  LOOP = false: one wave per span of 2048 columns (the
-// launcher guarantees blockDim = 64 * nspans); the wave's loads go out before the tables are
-// staged, so both latencies overlap.  LOOP = true: waves stride over the spans.
-template <int B, int NB, bool LOOP, int MAXT>
+// One workgroup per group of 4 rows; its waves stride over the row's spans of 2048 columns.
+// A wave's first loads go out before the tables are staged, so both latencies overlap; later
+// spans are loaded after the previous one is consumed (other waves of the CU cover the latency;
+// a second register set for prefetching cost more in occupancy than it gained).
+template <int B, int NB, int MAXT>
 __global__ __launch_bounds__(MAXT) void gemv_kernel(const uint8_t *__restrict__ slices,
                                                      size_t slice_bytes,
                                                      const uint16_t *__restrict__ lut,
@@ -212,25 +213,26 @@ __global__ __launch_bounds__(MAXT) void gemv_kernel(const uint8_t *__restrict__ 
     u32x4 Q[B];
     u32x4 X[NB][4];
     // Loads of the lane's slice words and activations for one span (Section 5.2 step 1).
-    auto issue_loads = [&](int span, int nl) {
-        const size_t unit = (size_t)g * chunks + (size_t)span * kSpanLanes + lane;
+    auto issue_loads = [&](int span) {
+        const int rem = chunks - span * kSpanLanes;
+        const int nl = rem < kSpanLanes ? rem : kSpanLanes;
+        if (lane < nl) {
+            const size_t unit = (size_t)g * chunks + (size_t)span * kSpanLanes + lane;
 #pragma unroll
-        for (int s = 0; s < B; ++s)
-            Q[s] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4 *>(slices + (size_t)s * slice_bytes + unit * 16));
+            for (int s = 0; s < B; ++s)
+                Q[s] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4 *>(slices + (size_t)s * slice_bytes + unit * 16));
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int xr = nb < batch ? nb : batch - 1;
+            for (int nb = 0; nb < NB; ++nb) {
+                const int xr = nb < batch ? nb : batch - 1;
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
-                X[nb][t] = *reinterpret_cast<const u32x4 *>(x + (size_t)xr * K + (size_t)span * kSpanCols +
-                                                            t * 8 * nl + lane * 8);
+                for (int t = 0; t < 4; ++t)
+                    X[nb][t] = *reinterpret_cast<const u32x4 *>(
+                        x + (size_t)xr * K + (size_t)span * kSpanCols + t * 8 * nl + lane * 8);
+            }
         }
     };
-    auto lanes_of = [&](int span) {
-        const int rem = chunks - span * kSpanLanes;
-        return rem < kSpanLanes ? rem : kSpanLanes;
-    };
+    auto active = [&](int span) { return lane < chunks - span * kSpanLanes; };
 
     float acc[NB][kRowsPerGroup];
 #pragma unroll
@@ -238,23 +240,15 @@ __global__ __launch_bounds__(MAXT) void gemv_kernel(const uint8_t *__restrict__ 
 #pragma unroll
         for (int r = 0; r < kRowsPerGroup; ++r) acc[nb][r] = 0.f;
 
-    if constexpr (!LOOP) {
-        const int nl = lanes_of(wave);
-        const bool active = lane < nl;
-        if (active) issue_loads(wave, nl);
-        stage_tables<B>(tab, nat, lut, row0, M);
-        __syncthreads();
-        if (active) compute_unit<B, NB>(Q, X, tab, acc);
-    } else {
-        stage_tables<B>(tab, nat, lut, row0, M);
-        __syncthreads();
-        for (int span = wave; span < nspans; span += nwaves) {
-            const int nl = lanes_of(span);
-            if (lane < nl) {
-                issue_loads(span, nl);
-                compute_unit<B, NB>(Q, X, tab, acc);
-            }
-        }
+    int span = wave; // the launcher guarantees nwaves <= nspans
+    issue_loads(span);
+    stage_tables<B>(tab, nat, lut, row0, M);
+    __syncthreads();
+    while (true) {
+        if (active(span)) compute_unit<B, NB>(Q, X, tab, acc);
+        span += nwaves;
+        if (span >= nspans) break;
+        issue_loads(span);
     }
 
     // ---- reduce over lanes, then over the waves of the group (fixed order: deterministic)
@@ -281,22 +275,19 @@ __global__ __launch_bounds__(MAXT) void gemv_kernel(const uint8_t *__restrict__ 
 template <int B, int NB>
 static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
 {
-    // batch 1 and 2 fit 128 registers per lane, so a group may have up to 16 waves;
-    // batch 4 and 8 keep 4 or 8 activation rows in registers and are capped at 4 waves.
-    constexpr int kMaxWaves = NB <= 2 ? 16 : 4;
+    // Up to 8 waves per group at batch 1 and 2 (measured best across the Llama shapes: long rows
+    // then take two spans per wave); batch 4 and 8 hold 4 or 8 activation rows in registers and
+    // are capped at 4 waves.
+    constexpr int kMaxWaves = NB <= 2 ? 8 : 4;
     constexpr int kMaxThreads = 64 * kMaxWaves;
     const int groups = padded_rows(a.M) / kRowsPerGroup;
     const int chunks = a.K / kChunkSlots;
     const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
-    int cap = kMaxWaves;
-    if (a.waves_per_group > 0 && a.waves_per_group < cap) cap = a.waves_per_group;
-    if (nspans <= cap) {
-        hipLaunchKernelGGL((gemv_kernel<B, NB, false, kMaxThreads>), dim3(groups), dim3(64 * nspans), 0,
-                           stream, a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
-    } else {
-        hipLaunchKernelGGL((gemv_kernel<B, NB, true, kMaxThreads>), dim3(groups), dim3(64 * cap), 0,
-                           stream, a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
-    }
+    int nw = kMaxWaves;
+    if (a.waves_per_group > 0 && a.waves_per_group < nw) nw = a.waves_per_group;
+    if (nw > nspans) nw = nspans;
+    hipLaunchKernelGGL((gemv_kernel<B, NB, kMaxThreads>), dim3(groups), dim3(64 * nw), 0, stream,
+                       a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
     return hipGetLastError();
 }
 
