@@ -35,6 +35,40 @@ __device__ __forceinline__ uint32_t bitsel(uint32_t m, uint32_t a, uint32_t b)
     asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(d) : "s"(m), "v"(a), "v"(b));
     return d;
 }
+// (byte J of v) & mask, and (byte J of v) << 1: one SDWA instruction each.  They turn a byte of a
+// merged index word into an LDS address.
+template <int J> __device__ __forceinline__ uint32_t byte_and(uint32_t v, uint32_t mask)
+{
+    uint32_t d;
+    if constexpr (J == 0)
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:DWORD" : "=v"(d) : "v"(v), "s"(mask));
+    else if constexpr (J == 1)
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD" : "=v"(d) : "v"(v), "s"(mask));
+    else if constexpr (J == 2)
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:DWORD" : "=v"(d) : "v"(v), "s"(mask));
+    else
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:DWORD" : "=v"(d) : "v"(v), "s"(mask));
+    return d;
+}
+template <int J> __device__ __forceinline__ uint32_t byte_shl1(uint32_t v, uint32_t one)
+{
+    uint32_t d;
+    if constexpr (J == 0)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(d) : "v"(one), "v"(v));
+    else if constexpr (J == 1)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(d) : "v"(one), "v"(v));
+    else if constexpr (J == 2)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(d) : "v"(one), "v"(v));
+    else
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(d) : "v"(one), "v"(v));
+    return d;
+}
+template <int B, int J> __device__ __forceinline__ uint32_t byte_to_addr(uint32_t v, uint32_t mask, uint32_t one)
+{
+    if constexpr (B == 8) return byte_shl1<J>(v, one);
+    else return byte_and<J>(v, mask);
+}
+
 __device__ __forceinline__ uint32_t rotr_v(uint32_t v, int r)
 {
     return (r & 31) ? __builtin_amdgcn_alignbit(v, v, r & 31) : v;
@@ -64,35 +98,95 @@ template <int ctrl, int row_mask> __device__ __forceinline__ float dpp_add(float
     int t = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, row_mask, 0xf, false);
     return v + __builtin_bit_cast(float, t);
 }
-// Sum over the 64 lanes of a wave; the total ends up in lane 63.
-__device__ __forceinline__ float wave_sum_to_lane63(float v)
+template <int ctrl> __device__ __forceinline__ float dpp_get(float v)
 {
-    v = dpp_add<0xB1, 0xf>(v);  // quad_perm [1,0,3,2]
-    v = dpp_add<0x4E, 0xf>(v);  // quad_perm [2,3,0,1]
-    v = dpp_add<0x141, 0xf>(v); // row_half_mirror
-    v = dpp_add<0x140, 0xf>(v); // row_mirror: every lane of a row of 16 holds the row sum
-    v = dpp_add<0x142, 0xa>(v); // row_bcast15 into rows 1 and 3
-    v = dpp_add<0x143, 0xc>(v); // row_bcast31 into rows 2 and 3
-    return v;
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true));
+}
+// Reduce the four per-row accumulators of a lane over each DPP row of 16 lanes at once.  Two
+// exchange steps leave one accumulator per lane (lane bits 0,1 select which: 0 -> row 0,
+// 1 -> row 2, 2 -> row 1, 3 -> row 3), two row shifts add the four quads.  On return lanes 12..15
+// of every DPP row hold that row's partial sums; 11 operations instead of 4 full reductions.
+__device__ __forceinline__ float reduce4_in_dpp_rows(const float (&a)[kRowsPerGroup], int lane)
+{
+    const bool odd = lane & 1, hi = lane & 2;
+    const float keep0 = odd ? a[2] : a[0], send0 = odd ? a[0] : a[2];
+    const float keep1 = odd ? a[3] : a[1], send1 = odd ? a[1] : a[3];
+    const float b0 = keep0 + dpp_get<0xB1>(send0); // quad_perm [1,0,3,2]
+    const float b1 = keep1 + dpp_get<0xB1>(send1);
+    const float keep = hi ? b1 : b0, send = hi ? b0 : b1;
+    float c = keep + dpp_get<0x4E>(send);          // quad_perm [2,3,0,1]
+    c += dpp_get<0x114>(c);                        // row_shr:4 (0 shifted in)
+    c += dpp_get<0x118>(c);                        // row_shr:8
+    return c;
 }
 
-// Copy the 4 rows' tables of this group from global memory into their LDS image.
+// Staging of the 4 rows' tables of a group, split in two so that the global loads can be issued
+// before the (much larger) slice loads and the LDS writes after them: vector-memory loads return
+// in order, so a table load issued last would only be usable once every slice load had landed.
+template <int B> struct StagedTable {
+    u32x4 v[2]; // B >= 6: up to two 16-byte pieces per thread; B <= 5: one dword in v[0].x
+};
+
+// All loads here are unconditional (indices clamped, unused results dropped or zeroed afterwards):
+// with no branch between them and the slice loads the compiler can count outstanding loads
+// exactly and waits for the table loads only.
 template <int B>
-__device__ __forceinline__ void stage_tables(uint8_t *tab, uint16_t *nat, const uint16_t *__restrict__ lut,
-                                             int row0, int M)
+__device__ __forceinline__ void stage_tables_load(StagedTable<B> &st, const uint16_t *__restrict__ lut, int row0, int M)
 {
     using T = Table<B>;
     constexpr int TB = T::kRowBytes;
     const int tid = threadIdx.x, nth = blockDim.x;
+    const int last_row = M - 1 - row0; // >= 0
     if constexpr (B == 3) {
-        // natural 8-entry rows first, then the 64-entry table of centroid pairs: pair index bit 2k
-        // is code bit k of the even slot, bit 2k+1 is code bit k of the odd slot.
-        if (tid < kRowsPerGroup * 4) {
-            const int r = tid >> 2;
-            uint32_t v = 0;
-            if (row0 + r < M) v = reinterpret_cast<const uint32_t *>(lut + (size_t)row0 * 8)[tid];
-            reinterpret_cast<uint32_t *>(nat)[tid] = v;
+        // natural 8-entry rows: 4 rows x 4 dwords
+        const int i = tid < kRowsPerGroup * 4 ? tid : kRowsPerGroup * 4 - 1;
+        const int r = i >> 2;
+        const int rc = r < last_row ? r : last_row;
+        const uint32_t v = reinterpret_cast<const uint32_t *>(lut + (size_t)row0 * 8)[rc * 4 + (i & 3)];
+        st.v[0].x = r <= last_row ? v : 0u;
+    } else if constexpr (B >= 6) {
+        // stored order = LDS order, rows contiguous: 16-byte pieces
+        constexpr int kPerRow = TB / 16;
+        constexpr int kChunks = kRowsPerGroup * kPerRow;
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(lut + ((size_t)row0 << B));
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            int i = tid + it * nth;
+            i = i < kChunks ? i : kChunks - 1;
+            const int r = i / kPerRow;
+            const int rc = r < last_row ? r : last_row;
+            const u32x4 v = src[rc * kPerRow + i % kPerRow];
+            st.v[it] = r <= last_row ? v : u32x4{0, 0, 0, 0};
         }
+    } else {
+        // B = 4, 5: two stored entries per dword
+        constexpr int kDwordsPerRow = (1 << B) / 2;
+        constexpr int kDwords = kRowsPerGroup * kDwordsPerRow;
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(lut + ((size_t)row0 << B));
+        const int i = tid < kDwords ? tid : kDwords - 1;
+        const int r = i / kDwordsPerRow;
+        const int rc = r < last_row ? r : last_row;
+        const uint32_t v = src[rc * kDwordsPerRow + i % kDwordsPerRow];
+        st.v[0].x = r <= last_row ? v : 0u;
+    }
+}
+
+// The LDS writes are unconditional as well (threads without a piece write a 16-byte dummy area
+// behind the tables): a conditional store would pull its load down into the branch, behind the
+// slice loads.
+template <int B>
+__device__ __forceinline__ void stage_tables_store(const StagedTable<B> &st, uint8_t *tab, uint16_t *nat)
+{
+    using T = Table<B>;
+    constexpr int TB = T::kRowBytes;
+    constexpr int kDummy = kRowsPerGroup * TB; // byte offset of the dummy area inside tab
+    const int tid = threadIdx.x, nth = blockDim.x;
+    if constexpr (B == 3) {
+        // the 64-entry table of centroid pairs: pair index bit 2k is code bit k of the even slot,
+        // bit 2k+1 is code bit k of the odd slot.
+        uint32_t *dst = tid < kRowsPerGroup * 4 ? reinterpret_cast<uint32_t *>(nat) + tid
+                                                : reinterpret_cast<uint32_t *>(tab + kDummy);
+        *dst = st.v[0].x;
         __syncthreads();
         for (int i = tid; i < kRowsPerGroup * 64; i += nth) {
             const int r = i >> 6, i6 = i & 63;
@@ -102,27 +196,19 @@ __device__ __forceinline__ void stage_tables(uint8_t *tab, uint16_t *nat, const 
             *reinterpret_cast<uint32_t *>(tab + r * TB + i6 * 4) = v;
         }
     } else if constexpr (B >= 6) {
-        // stored order = LDS order, rows contiguous: straight 16-byte copies
         constexpr int kChunks = kRowsPerGroup * TB / 16;
-        const uint4 *src = reinterpret_cast<const uint4 *>(lut + ((size_t)row0 << B));
-        for (int i = tid; i < kChunks; i += nth) {
-            const int r = i / (TB / 16);
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (row0 + r < M) v = src[i];
-            reinterpret_cast<uint4 *>(tab)[i] = v;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int i = tid + it * nth;
+            reinterpret_cast<u32x4 *>(tab)[i < kChunks ? i : kChunks] = st.v[it];
         }
     } else {
-        // B = 4, 5: two stored entries per dword, spread to their dword-strided LDS addresses
+        // spread the two entries of a dword to their dword-strided LDS addresses
         constexpr int kDwordsPerRow = (1 << B) / 2;
-        const uint32_t *src = reinterpret_cast<const uint32_t *>(lut + ((size_t)row0 << B));
-        for (int i = tid; i < kRowsPerGroup * kDwordsPerRow; i += nth) {
-            const int r = i / kDwordsPerRow, k = i % kDwordsPerRow;
-            uint32_t v = 0;
-            if (row0 + r < M) v = src[i];
-            uint8_t *dst = tab + r * TB + T::stored_addr(2 * k);
-            *reinterpret_cast<uint16_t *>(dst) = (uint16_t)v;
-            *reinterpret_cast<uint16_t *>(dst + 4) = (uint16_t)(v >> 16);
-        }
+        const int r = tid / kDwordsPerRow, k = tid % kDwordsPerRow;
+        uint8_t *dst = tid < kRowsPerGroup * kDwordsPerRow ? tab + r * TB + T::stored_addr(2 * k) : tab + kDummy;
+        *reinterpret_cast<uint16_t *>(dst) = (uint16_t)st.v[0].x;
+        *reinterpret_cast<uint16_t *>(dst + 4) = (uint16_t)(st.v[0].x >> 16);
     }
 }
 
@@ -134,6 +220,8 @@ __device__ __forceinline__ void compute_unit(const u32x4 (&Q)[B], const u32x4 (&
 {
     using T = Table<B>;
     constexpr int TB = T::kRowBytes;
+    uint32_t one = 1; // shift amount of the B = 8 address form, kept in a register
+    asm("" : "+v"(one));
 #pragma unroll
     for (int r = 0; r < kRowsPerGroup; ++r) {
         const uint8_t *trow = tab + r * TB;
@@ -144,10 +232,11 @@ __device__ __forceinline__ void compute_unit(const u32x4 (&Q)[B], const u32x4 (&
                 uint32_t v = bitsel(rotl_c(0x30303030u, u), Q[1][r], Q[2][r]);
                 v = bitsel(rotl_c(0xC0C0C0C0u, u), Q[0][r], v);
                 v = rotr_v(v, u);
+                const uint32_t a4[4] = {byte_and<0>(v, 0xFCu), byte_and<1>(v, 0xFCu), byte_and<2>(v, 0xFCu),
+                                        byte_and<3>(v, 0xFCu)};
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const uint32_t a = (v >> (8 * j)) & 0xFCu;
-                    const uint32_t w = *reinterpret_cast<const uint32_t *>(trow + a);
+                    const uint32_t w = *reinterpret_cast<const uint32_t *>(trow + a4[j]);
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
                         // (copy the vector element first: a bit cast applied directly to a vector
@@ -166,11 +255,11 @@ __device__ __forceinline__ void compute_unit(const u32x4 (&Q)[B], const u32x4 (&
                 for (int s = B - 2; s >= 0; --s)
                     v = bitsel(rotl_c(0x01010101u, u + slice_rot(s)), Q[s][r], v);
                 v = rotr_v(v, u);
+                const uint32_t a4[4] = {byte_to_addr<B, 0>(v, T::addr_mask(), one), byte_to_addr<B, 1>(v, T::addr_mask(), one),
+                                        byte_to_addr<B, 2>(v, T::addr_mask(), one), byte_to_addr<B, 3>(v, T::addr_mask(), one)};
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const uint32_t byte = (v >> (8 * j)) & 0xFFu;
-                    const uint32_t a = B == 8 ? (byte << 1) : (byte & T::addr_mask());
-                    const _Float16 w = *reinterpret_cast<const _Float16 *>(trow + a);
+                    const _Float16 w = *reinterpret_cast<const _Float16 *>(trow + a4[j]);
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
                         const uint32_t xw = X[nb][u >> 1][j];
@@ -185,11 +274,12 @@ __device__ __forceinline__ void compute_unit(const u32x4 (&Q)[B], const u32x4 (&
 }
 
 // One workgroup per group of 4 rows; its waves stride over the row's spans of 2048 columns.
-// A wave's first loads go out before the tables are staged, so both latencies overlap; later
+// The table loads go out first, then the wave's first slice loads, then the tables are written to
+// LDS while the slice loads are still in flight; later
 // spans are loaded after the previous one is consumed (other waves of the CU cover the latency;
 // a second register set for prefetching cost more in occupancy than it gained).
 template <int B, int NB, int MAXT>
-__global__ __launch_bounds__(MAXT) void gemv_kernel(const uint8_t *__restrict__ slices,
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 6))) void gemv_kernel(const uint8_t *__restrict__ slices,
                                                      size_t slice_bytes,
                                                      const uint16_t *__restrict__ lut,
                                                      const uint16_t *__restrict__ x,
@@ -198,9 +288,9 @@ __global__ __launch_bounds__(MAXT) void gemv_kernel(const uint8_t *__restrict__ 
 {
     using T = Table<B>;
     constexpr int TB = T::kRowBytes;
-    __shared__ __attribute__((aligned(16))) uint8_t tab[kRowsPerGroup * TB];
+    __shared__ __attribute__((aligned(16))) uint8_t tab[kRowsPerGroup * TB + 16]; // + dummy area
     __shared__ __attribute__((aligned(16))) uint16_t nat[kRowsPerGroup * 8];
-    __shared__ float red[MAXT / 64][kRowsPerGroup * NB];
+    __shared__ float red[MAXT / 64][NB][4][kRowsPerGroup]; // [wave][batch row][DPP row][lane & 3]
 
     const int g = blockIdx.x;
     const int lane = threadIdx.x & 63;
@@ -216,19 +306,24 @@ __global__ __launch_bounds__(MAXT) void gemv_kernel(const uint8_t *__restrict__ 
     auto issue_loads = [&](int span) {
         const int rem = chunks - span * kSpanLanes;
         const int nl = rem < kSpanLanes ? rem : kSpanLanes;
-        if (lane < nl) {
-            const size_t unit = (size_t)g * chunks + (size_t)span * kSpanLanes + lane;
+        {
+            // Lanes past the end of a ragged last span load what the last valid lane loads (and are
+            // masked out of the compute): no branch around the loads.
+            // wave-uniform base + 32-bit lane offset: the loads use the scalar-base address form
+            const uint8_t *sbase = slices + ((size_t)g * chunks + (size_t)span * kSpanLanes) * 16;
+            const uint32_t loff = (uint32_t)(lane < nl ? lane : nl - 1) * 16u;
 #pragma unroll
             for (int s = 0; s < B; ++s)
                 Q[s] = __builtin_nontemporal_load(
-                    reinterpret_cast<const u32x4 *>(slices + (size_t)s * slice_bytes + unit * 16));
+                    reinterpret_cast<const u32x4 *>(sbase + (size_t)s * slice_bytes + loff));
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const int xr = nb < batch ? nb : batch - 1;
+                const uint8_t *xbase =
+                    reinterpret_cast<const uint8_t *>(x + (size_t)xr * K + (size_t)span * kSpanCols);
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
-                    X[nb][t] = *reinterpret_cast<const u32x4 *>(
-                        x + (size_t)xr * K + (size_t)span * kSpanCols + t * 8 * nl + lane * 8);
+                    X[nb][t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)(t * 16 * nl) + loff);
             }
         }
     };
@@ -241,8 +336,10 @@ __global__ __launch_bounds__(MAXT) void gemv_kernel(const uint8_t *__restrict__ 
         for (int r = 0; r < kRowsPerGroup; ++r) acc[nb][r] = 0.f;
 
     int span = wave; // the launcher guarantees nwaves <= nspans
+    StagedTable<B> st;
+    stage_tables_load<B>(st, lut, row0, M);
     issue_loads(span);
-    stage_tables<B>(tab, nat, lut, row0, M);
+    stage_tables_store<B>(st, tab, nat); // waits for the table loads only
     __syncthreads();
     while (true) {
         if (active(span)) compute_unit<B, NB>(Q, X, tab, acc);
@@ -253,17 +350,17 @@ __global__ __launch_bounds__(MAXT) void gemv_kernel(const uint8_t *__restrict__ 
 
     // ---- reduce over lanes, then over the waves of the group (fixed order: deterministic)
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int r = 0; r < kRowsPerGroup; ++r) {
-            const float s = wave_sum_to_lane63(acc[nb][r]);
-            if (lane == 63) red[wave][nb * kRowsPerGroup + r] = s;
-        }
+    for (int nb = 0; nb < NB; ++nb) {
+        const float c = reduce4_in_dpp_rows(acc[nb], lane);
+        if ((lane & 15) >= 12) red[wave][nb][lane >> 4][lane & 3] = c;
+    }
     __syncthreads();
     if (threadIdx.x < kRowsPerGroup * NB) {
         const int nb = threadIdx.x / kRowsPerGroup, r = threadIdx.x % kRowsPerGroup;
+        const int cls = ((r & 1) << 1) | (r >> 1); // lane & 3 that holds row r
         float s = 0.f;
-        for (int w = 0; w < nwaves; ++w) s += red[w][threadIdx.x];
+        for (int w = 0; w < nwaves; ++w)
+            for (int d = 0; d < 4; ++d) s += red[w][nb][d][cls];
         const int row = row0 + r;
         if (row < M && nb < batch) {
             const __half h = __float2half_rn(s);
