@@ -111,6 +111,14 @@ ap_status ap_unpack(const ap_matrix *h, uint8_t *idx_host_out, void *stream);
 ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int batch,
                   void *stream);
 
+/*
+ * Measurement aid, not part of the method: reads `bytes` (a multiple of 16384) of device memory
+ * with the same instruction and access shape as the GEMV's slice loads (non-temporal 16-byte
+ * loads, 1 KB contiguous per wave) and discards them.  Profiling counters of HBM traffic are
+ * calibrated against this launch, whose byte count is known.  Asynchronous on `stream`.
+ */
+ap_status ap_probe_read(const void *dev_buf, size_t bytes, void *stream);
+
 /* Shape and supported bit-widths of a handle; any output pointer may be NULL. */
 ap_status ap_matrix_info(const ap_matrix *h, int *M, int *K, int *n, unsigned *lut_mask);
 

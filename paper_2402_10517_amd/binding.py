@@ -22,7 +22,8 @@ STATUS_NAMES = {0: "AP_OK", 1: "AP_ERR_INVALID_ARG", 2: "AP_ERR_SHAPE", 3: "AP_E
                 7: "AP_ERR_HIP"}
 
 EXPORTS = ["ap_packed_size", "ap_pack_host", "ap_unpack_host", "ap_blob_lut_entry",
-           "ap_read_extent", "ap_pack", "ap_attach", "ap_unpack", "ap_gemv", "ap_matrix_info",
+           "ap_read_extent", "ap_pack", "ap_attach", "ap_unpack", "ap_gemv", "ap_probe_read",
+           "ap_matrix_info",
            "ap_free", "ap_strerror"]
 
 
@@ -48,6 +49,7 @@ def _load():
     L.ap_attach.argtypes = [vp, sz, vp, ctypes.POINTER(vp)]
     L.ap_unpack.argtypes = [vp, vp, vp]
     L.ap_gemv.argtypes = [vp, ci, vp, vp, ci, vp]
+    L.ap_probe_read.argtypes = [vp, sz, vp]
     L.ap_matrix_info.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci),
                                  ctypes.POINTER(cu)]
     L.ap_free.argtypes = [vp]

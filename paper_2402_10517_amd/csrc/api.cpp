@@ -131,6 +131,15 @@ extern "C" ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void 
     return launch_gemv(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
+extern "C" ap_status ap_probe_read(const void *dev_buf, size_t bytes, void *stream)
+{
+    if (!dev_buf || bytes == 0 || bytes % 16384 || reinterpret_cast<uintptr_t>(dev_buf) % 16)
+        return AP_ERR_INVALID_ARG;
+    if (bytes / 16384 > 0x7fffffffu) return AP_ERR_INVALID_ARG;
+    return launch_probe_read(dev_buf, bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK
+                                                                                              : AP_ERR_HIP;
+}
+
 extern "C" ap_status ap_matrix_info(const ap_matrix *h, int *M, int *K, int *n, unsigned *lut_mask)
 {
     if (!handle_ok(h)) return AP_ERR_INVALID_ARG;

@@ -19,6 +19,7 @@ struct GemvArgs {
 };
 
 hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream);
+hipError_t launch_probe_read(const void *dev_buf, size_t bytes, hipStream_t stream);
 
 } // namespace apgemv
 #endif

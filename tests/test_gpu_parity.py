@@ -129,6 +129,24 @@ def test_adversarial_tables(B, b):
     pm.close()
 
 
+@pytest.mark.parametrize("batch", [1, 2, 8])
+@pytest.mark.parametrize("b", ALL_BITS)
+def test_subnormal_centroids_are_not_flushed(B, b, batch):
+    # every centroid is a binary16 subnormal (k * 2^-24), activations are large: a path that
+    # flushed subnormal inputs to zero would return 0 where the result is of order 10
+    M, K = 20, 2048 + 64
+    rng = np.random.default_rng(100 + b)
+    idx = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+    lut = (rng.integers(1, 1024, size=(M, 1 << b)).astype(np.uint16)).view(np.float16)
+    x = np.full((batch, K), 512.0, dtype=np.float16)
+    x[:, ::3] = -256.0
+    pm = B.ap_pack(idx, {b: lut})
+    y = run_gemv(pm, b, x)
+    assert np.all(np.abs(y.astype(np.float64)) > 0.05)
+    check_against_oracle(y, idx, lut, b, x)
+    pm.close()
+
+
 def test_dispatch_sequence_without_repacking_and_determinism(B, tiny):
     import torch
     idx, luts, x, pm = tiny
