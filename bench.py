@@ -31,6 +31,67 @@ MEASURED_TRAFFIC_BYTES = {3: 13768788, 4: 18264593, 5: 22936475, 6: 27811037, 7:
 COPIES = 7      # device copies of every packed matrix (rotation period)
 
 
+def decode_step(args, np, torch, B, inputs, dev):
+    """Config 4: all 224 matrices of a 7B-shaped model resident, one bit-width per decode step.
+
+    Layer 0's seven matrices are drawn and packed; the other 31 layers are device copies of them
+    (distinct addresses are what the memory system sees; 6.5 GB of slices + 1.4 GB of tables).
+    Each step issues the 224 batch-1 GEMVs of one token at that step's bit-width, replayed from one
+    HIP graph per bit-width; no repacking between steps.
+    """
+    layer = []
+    for k, (M, K) in enumerate(inputs.DECODE_LAYER_SHAPES):
+        idx, luts, x = inputs.make_case(4, M, K, salt=k)
+        pm = B.ap_pack(idx, luts, device=dev)
+        xd = torch.from_numpy(x).to(dev)
+        yd = torch.empty((1, M), dtype=torch.float16, device=dev)
+        layer.append((M, K, pm, xd, yd))
+    model = [[(M, K, pm if l == 0 else pm.clone(), xd, yd) for (M, K, pm, xd, yd) in layer]
+             for l in range(inputs.DECODE_LAYERS)]
+    cap = torch.cuda.Stream()
+    sp = ctypes.c_void_p(cap.cuda_stream)
+
+    def issue(b):
+        for lay in model:
+            for (M, K, pm, xd, yd) in lay:
+                if B.lib.ap_gemv(pm.handle, b, xd.data_ptr(), yd.data_ptr(), 1, sp) != 0:
+                    raise RuntimeError("ap_gemv failed")
+
+    graphs = {}
+    with torch.cuda.stream(cap):
+        for b in range(3, 9):
+            issue(b)
+            cap.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=cap):
+                issue(b)
+            graphs[b] = g
+    torch.cuda.synchronize()
+    seq = inputs.decode_bit_sequence(64)
+    per_b = {b: [] for b in range(3, 9)}
+    for b in seq[:6]:
+        graphs[b].replay()
+    torch.cuda.synchronize()
+    for b in seq:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graphs[b].replay()
+        e1.record()
+        torch.cuda.synchronize()
+        per_b[b].append(e0.elapsed_time(e1) * 1e3)
+    rows = []
+    for b in range(3, 9):
+        nbytes = inputs.DECODE_LAYERS * sum(inputs.algorithmic_bytes(M, K, b) for (M, K) in inputs.DECODE_LAYER_SHAPES)
+        if per_b[b]:
+            us = float(np.median(per_b[b]))
+            rows.append(dict(b=b, steps=len(per_b[b]), us_per_step=round(us, 1), bytes=nbytes,
+                             GBps=round(nbytes / us / 1e3, 1), frac_of_peak=round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)))
+            print("  decode step b=%d: %8.1f us (median of %d)  %7.1f GB/s  %5.1f%% of 8 TB/s" %
+                  (b, us, len(per_b[b]), nbytes / us / 1e3, 100 * nbytes / us / 1e3 / HBM_PEAK_GBPS), file=sys.stderr)
+    print(json.dumps(dict(metric="7B-shaped decode step latency by bit-width (224 batch-1 GEMVs per step)",
+                          unit="us/step", n_gpus=1, data="synthetic", sequence=seq, per_bit_width=rows)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -42,6 +103,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 5],
                     help="benchmark configuration to run (default 2 = the headline workload)")
     ap.add_argument("--batch", type=int, default=1, help="batch size (exploration only; headline is 1)")
+    ap.add_argument("--decode-step", action="store_true",
+                    help="instead of the headline line: the 7B-shaped decode step (32 layers x 7 matrices packed "
+                         "once, a seeded sequence of per-step bit-widths); prints one JSON line with per-b latency")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -58,6 +122,9 @@ def main():
         sys.exit(3)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.decode_step:
+        decode_step(args, np, torch, B, inputs, dev)
+        return
     cfg = inputs.CONFIGS[args.config]
     shapes = cfg["shapes"]
     batch = args.batch

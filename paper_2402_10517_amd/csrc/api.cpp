@@ -16,15 +16,22 @@ struct ap_matrix {
     BlobHeader hdr;
     uint8_t *dev;
     int waves_per_group;
+    int row_groups_per_wg;
 };
 static constexpr uint32_t kHandleTag = 0x41504d58u;
 
 static bool handle_ok(const ap_matrix *h) { return h && h->tag == kHandleTag && h->dev; }
 
+// Tuning overrides for experiments: waves per row group, row groups per workgroup.
 static int env_waves()
 {
     const char *e = std::getenv("APGEMV_WAVES");
     return e ? std::atoi(e) : 0;
+}
+static int env_row_groups()
+{
+    const char *e = std::getenv("APGEMV_ROW_GROUPS");
+    return e ? std::atoi(e) : -1;
 }
 
 extern "C" ap_status ap_pack(const uint8_t *idx_host, int M, int K, int n,
@@ -63,6 +70,7 @@ extern "C" ap_status ap_pack(const uint8_t *idx_host, int M, int K, int n,
     h->hdr = hdr;
     h->dev = static_cast<uint8_t *>(dev_buf);
     h->waves_per_group = env_waves();
+    h->row_groups_per_wg = env_row_groups();
     *out = h;
     return AP_OK;
 }
@@ -84,6 +92,7 @@ extern "C" ap_status ap_attach(void *dev_buf, size_t dev_buf_bytes, void *stream
     h->hdr = hdr;
     h->dev = static_cast<uint8_t *>(dev_buf);
     h->waves_per_group = env_waves();
+    h->row_groups_per_wg = env_row_groups();
     *out = h;
     return AP_OK;
 }
@@ -128,6 +137,7 @@ extern "C" ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void 
     a.b = b;
     a.batch = batch;
     a.waves_per_group = h->waves_per_group;
+    a.row_groups_per_wg = h->row_groups_per_wg;
     return launch_gemv(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 

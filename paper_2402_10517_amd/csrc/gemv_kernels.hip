@@ -386,13 +386,134 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 6))) vo
     }
 }
 
+// Variant for matrices with many rows and for batches: one workgroup owns up to kMaxRowGroups
+// consecutive groups of 4 rows and each wave keeps its activations (one span, all batch rows) in
+// registers across them, so activation traffic through the caches drops by that factor and the
+// per-wave set-up is paid once.  The slice words of the next group are loaded while the current
+// group is processed.  Requires one wave per span (the launcher checks).
+constexpr int kMaxRowGroups = 4;
+
+template <int B, int NB, int MAXT>
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(1, 6))) void gemv_rows_kernel(
+    const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
+    const uint16_t *__restrict__ x, uint16_t *__restrict__ y, int M, int K, int batch, int rg_per_wg)
+{
+    using T = Table<B>;
+    constexpr int TB = T::kRowBytes;
+    constexpr int kGroupBytes = kRowsPerGroup * TB;
+    __shared__ __attribute__((aligned(16))) uint8_t tab[kMaxRowGroups * kGroupBytes];
+    __shared__ __attribute__((aligned(16))) uint16_t nat[kMaxRowGroups * kRowsPerGroup * 8];
+    __shared__ float red[MAXT / 64][kMaxRowGroups][NB][4][kRowsPerGroup];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int nwaves = blockDim.x >> 6;
+    const int tid = threadIdx.x, nth = blockDim.x;
+    const int groups = (M + kRowsPerGroup - 1) / kRowsPerGroup;
+    const int g0 = blockIdx.x * rg_per_wg;
+    const int ng = groups - g0 < rg_per_wg ? groups - g0 : rg_per_wg;
+    const int row0 = g0 * kRowsPerGroup;
+    const int nrows = M - row0 < ng * kRowsPerGroup ? M - row0 : ng * kRowsPerGroup; // valid rows here
+    const int chunks = K / kChunkSlots;
+    const int span = wave; // one wave per span
+    const int rem = chunks - span * kSpanLanes;
+    const int nl = rem < kSpanLanes ? rem : kSpanLanes;
+    const bool active = lane < nl;
+    const uint32_t loff = (uint32_t)(active ? lane : nl - 1) * 16u;
+
+    auto load_q = [&](u32x4 (&Q)[B], int rg) {
+        const uint8_t *sbase = slices + ((size_t)(g0 + rg) * chunks + (size_t)span * kSpanLanes) * 16;
+#pragma unroll
+        for (int s = 0; s < B; ++s)
+            Q[s] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4 *>(sbase + (size_t)s * slice_bytes + loff));
+    };
+
+    u32x4 X[NB][4];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int xr = nb < batch ? nb : batch - 1;
+        const uint8_t *xbase = reinterpret_cast<const uint8_t *>(x + (size_t)xr * K + (size_t)span * kSpanCols);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            X[nb][t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)(t * 16 * nl) + loff);
+    }
+    u32x4 QA[B], QB[B];
+    load_q(QA, 0);
+
+    // ---- tables of all the groups of this workgroup (rows are contiguous in the stored tables)
+    if constexpr (B == 3) {
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(lut + (size_t)row0 * 8);
+        for (int i = tid; i < ng * kRowsPerGroup * 4; i += nth)
+            reinterpret_cast<uint32_t *>(nat)[i] = (i >> 2) < nrows ? src[i] : 0u;
+        __syncthreads();
+        for (int i = tid; i < ng * kRowsPerGroup * 64; i += nth) {
+            const int r = i >> 6, i6 = i & 63;
+            const int a = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
+            const int c = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
+            const uint32_t v = (uint32_t)nat[r * 8 + a] | ((uint32_t)nat[r * 8 + c] << 16);
+            *reinterpret_cast<uint32_t *>(tab + r * TB + i6 * 4) = v;
+        }
+    } else if constexpr (B >= 6) {
+        constexpr int kPerRow = TB / 16;
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(lut + ((size_t)row0 << B));
+        for (int i = tid; i < ng * kRowsPerGroup * kPerRow; i += nth)
+            reinterpret_cast<u32x4 *>(tab)[i] = i / kPerRow < nrows ? src[i] : u32x4{0, 0, 0, 0};
+    } else {
+        constexpr int kDwordsPerRow = (1 << B) / 2;
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(lut + ((size_t)row0 << B));
+        for (int i = tid; i < ng * kRowsPerGroup * kDwordsPerRow; i += nth) {
+            const int r = i / kDwordsPerRow, k = i % kDwordsPerRow;
+            const uint32_t v = r < nrows ? src[i] : 0u;
+            uint8_t *dst = tab + r * TB + T::stored_addr(2 * k);
+            *reinterpret_cast<uint16_t *>(dst) = (uint16_t)v;
+            *reinterpret_cast<uint16_t *>(dst + 4) = (uint16_t)(v >> 16);
+        }
+    }
+    __syncthreads();
+
+    auto process = [&](const u32x4 (&Q)[B], int rg) {
+        float acc[NB][kRowsPerGroup];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < kRowsPerGroup; ++r) acc[nb][r] = 0.f;
+        if (active) compute_unit<B, NB>(Q, X, tab + rg * kGroupBytes, acc);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const float c = reduce4_in_dpp_rows(acc[nb], lane);
+            if ((lane & 15) >= 12) red[wave][rg][nb][lane >> 4][lane & 3] = c;
+        }
+    };
+    for (int rg = 0; rg < ng; rg += 2) {
+        if (rg + 1 < ng) load_q(QB, rg + 1);
+        process(QA, rg);
+        if (rg + 1 >= ng) break;
+        if (rg + 2 < ng) load_q(QA, rg + 2);
+        process(QB, rg + 1);
+    }
+    __syncthreads();
+    for (int i = tid; i < ng * kRowsPerGroup * NB; i += nth) {
+        const int rg = i / (kRowsPerGroup * NB), nb = (i / kRowsPerGroup) % NB, r = i % kRowsPerGroup;
+        const int cls = ((r & 1) << 1) | (r >> 1); // lane & 3 that holds row r
+        float s = 0.f;
+        for (int w = 0; w < nwaves; ++w)
+            for (int d = 0; d < 4; ++d) s += red[w][rg][nb][d][cls];
+        const int row = row0 + rg * kRowsPerGroup + r;
+        if (row < M && nb < batch) {
+            const __half h = __float2half_rn(s);
+            y[(size_t)nb * M + row] = __builtin_bit_cast(uint16_t, h);
+        }
+    }
+}
+
 template <int B, int NB>
 static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
 {
     // Up to 8 waves per group at batch 1 and 2 (measured best across the Llama shapes: long rows
     // then take two spans per wave); batch 4 and 8 hold 4 or 8 activation rows in registers and
     // are capped at 4 waves.
-    constexpr int kMaxWaves = NB <= 2 ? 8 : 4;
+    constexpr int kMaxWaves = NB <= 4 ? 8 : 4;
     constexpr int kMaxThreads = 64 * kMaxWaves;
     const int groups = padded_rows(a.M) / kRowsPerGroup;
     const int chunks = a.K / kChunkSlots;
@@ -400,6 +521,17 @@ static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
     int nw = kMaxWaves;
     if (a.waves_per_group > 0 && a.waves_per_group < nw) nw = a.waves_per_group;
     if (nw > nspans) nw = nspans;
+    // several row groups per workgroup when every span has its own wave and there are enough
+    // groups to keep the device full
+    int rg = a.row_groups_per_wg;
+    if (rg < 0) rg = (nspans <= kMaxWaves && groups >= 2048 && NB >= 2) ? kMaxRowGroups : 1;
+    if (rg > kMaxRowGroups) rg = kMaxRowGroups;
+    if (rg > 1 && nspans <= kMaxWaves) {
+        hipLaunchKernelGGL((gemv_rows_kernel<B, NB, kMaxThreads>), dim3((groups + rg - 1) / rg),
+                           dim3(64 * nspans), 0, stream, a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M,
+                           a.K, a.batch, rg);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL((gemv_kernel<B, NB, kMaxThreads>), dim3(groups), dim3(64 * nw), 0, stream,
                        a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
     return hipGetLastError();

@@ -16,6 +16,7 @@ struct GemvArgs {
     uint16_t *y;           // device: batch * M binary16
     int M, K, b, batch;
     int waves_per_group;   // 0 = choose from the shape
+    int row_groups_per_wg; // -1 = choose from the shape; 1 = one group of 4 rows per workgroup
 };
 
 hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream);

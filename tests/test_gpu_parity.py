@@ -147,6 +147,21 @@ def test_subnormal_centroids_are_not_flushed(B, b, batch):
     pm.close()
 
 
+@pytest.mark.parametrize("rg", [2, 3, 4])
+@pytest.mark.parametrize("batch", [1, 2, 5, 8])
+def test_several_row_groups_per_workgroup(B, monkeypatch, rg, batch):
+    # the variant that keeps activations in registers across row groups, forced on small ragged
+    # shapes: rows not a multiple of 4*rg, a ragged last span, 1..4 waves per group
+    monkeypatch.setenv("APGEMV_ROW_GROUPS", str(rg))
+    for (M, K) in [(4 * rg * 3 + 5, 2048 + 160), (7, 96), (4 * rg + 1, 3 * 2048 + 32 * 17)]:
+        idx, luts, x = inputs.make_case(18, M, K, batch=batch, sigma=0.01)
+        pm = B.ap_pack(idx, luts)
+        for b in ALL_BITS:
+            y = run_gemv(pm, b, x)
+            check_against_oracle(y, idx, luts[b], b, x)
+        pm.close()
+
+
 def test_dispatch_sequence_without_repacking_and_determinism(B, tiny):
     import torch
     idx, luts, x, pm = tiny
