@@ -157,37 +157,51 @@ def main():
     step_bytes = sum(inputs.algorithmic_bytes(cs["M"], cs["K"], b, batch) for cs in cases for b in bits)
 
     graphs = None
+    cycle_graph = None
     if not args.no_graph:
-        # one captured graph per rotation phase; side stream as torch requires for capture
+        # one captured graph per rotation phase, plus one graph holding a whole rotation cycle
+        # (COPIES consecutive steps) so that long runs pay the replay cost once per cycle;
+        # captured on a side stream as torch requires
         graphs = []
         cap = torch.cuda.Stream()
-        for phase in range(COPIES):
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.stream(cap):
-                sp_save = sp
-                sp = ctypes.c_void_p(cap.cuda_stream)
+        sp_save = sp
+        with torch.cuda.stream(cap):
+            sp = ctypes.c_void_p(cap.cuda_stream)
+            for phase in range(COPIES):
                 issue_step(phase)          # eager warm-up on the capture stream
-                cap.synchronize()
+            cap.synchronize()
+            for phase in range(COPIES):
+                g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g, stream=cap):
                     issue_step(phase)
-                sp = sp_save
-            graphs.append(g)
+                graphs.append(g)
+            cycle_graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(cycle_graph, stream=cap):
+                for phase in range(COPIES):
+                    issue_step(phase)
+        sp = sp_save
         torch.cuda.synchronize()
 
-    def run_step(i):
-        if graphs is not None:
-            graphs[i % COPIES].replay()
-        else:
-            issue_step(i % COPIES)
+    def run_steps(first, count):
+        """Steps first .. first+count-1 in order; whole rotation cycles are replayed as one graph."""
+        i = first
+        while i < first + count:
+            if graphs is None:
+                issue_step(i % COPIES)
+                i += 1
+            elif i % COPIES == 0 and i + COPIES <= first + count:
+                cycle_graph.replay()
+                i += COPIES
+            else:
+                graphs[i % COPIES].replay()
+                i += 1
 
-    for i in range(args.warmup):
-        run_step(i)
+    run_steps(0, args.warmup)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
-    for i in range(args.steps):
-        run_step(args.warmup + i)
+    run_steps(args.warmup, args.steps)
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3

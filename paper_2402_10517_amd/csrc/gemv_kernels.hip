@@ -311,7 +311,7 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 6))) vo
 
     const int g = blockIdx.x;
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform, kept in an SGPR
     const int nwaves = blockDim.x >> 6;
     const int row0 = g * kRowsPerGroup;
     const int chunks = K / kChunkSlots;
@@ -406,7 +406,7 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(1, 6))) vo
     __shared__ float red[MAXT / 64][kMaxRowGroups][NB][4][kRowsPerGroup];
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform, kept in an SGPR
     const int nwaves = blockDim.x >> 6;
     const int tid = threadIdx.x, nth = blockDim.x;
     const int groups = (M + kRowsPerGroup - 1) / kRowsPerGroup;
