@@ -31,6 +31,64 @@ MEASURED_TRAFFIC_BYTES = {3: 13768788, 4: 18264593, 5: 22936475, 6: 27811037, 7:
 COPIES = 7      # device copies of every packed matrix (rotation period)
 
 
+def large_batch(args, np, torch, B, inputs, dev):
+    """Dequantise kernel (HBM-bound: reads b/8 bytes, writes 2 bytes per weight) and the
+    dequantise + rocBLAS FP16 GEMM path, on the Llama-2-7B shapes."""
+    sp = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    rows = []
+    for (M, K) in inputs.CONFIGS[2]["shapes"]:
+        idx, luts, _ = inputs.make_case(2, M, K)
+        pm = B.ap_pack(idx, luts, device=dev)
+        copies = [pm] + [pm.clone() for _ in range(COPIES - 1)]
+        works = [torch.empty(M * K * 2, dtype=torch.uint8, device=dev) for _ in range(4)]
+        for b in range(3, 9):
+            def issue(n):
+                for r in range(n):
+                    st = B.lib.ap_dequantize(copies[r % COPIES].handle, b, works[r % 4].data_ptr(), sp)
+                    if st != 0:
+                        raise RuntimeError("ap_dequantize failed")
+            issue(8)
+            torch.cuda.synchronize()
+            samples = []
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                issue(28)
+                e1.record()
+                torch.cuda.synchronize()
+                samples.append(e0.elapsed_time(e1) * 1e3 / 28)
+            us = sorted(samples)[1]
+            nbytes = M * K * b // 8 + M * (2 << b) + M * K * 2
+            row = dict(M=M, K=K, b=b, dequant_us=round(us, 2), dequant_bytes=nbytes,
+                       dequant_GBps=round(nbytes / us / 1e3, 1), frac_of_peak=round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4))
+            if b in (4, 8):
+                for batch in (16, 64, 256, 512):
+                    x = torch.randn((batch, K), dtype=torch.float16, device=dev)
+                    y = torch.empty((batch, M), dtype=torch.float16, device=dev)
+                    for r in range(3):
+                        B.lib.ap_gemm(pm.handle, b, x.data_ptr(), y.data_ptr(), batch, works[0].data_ptr(),
+                                      works[0].numel(), sp)
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for r in range(10):
+                        B.lib.ap_gemm(copies[r % COPIES].handle, b, x.data_ptr(), y.data_ptr(), batch,
+                                      works[r % 4].data_ptr(), works[0].numel(), sp)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    row["gemm_us_batch%d" % batch] = round(e0.elapsed_time(e1) * 1e3 / 10, 2)
+            rows.append(row)
+            print("  %5dx%-5d b=%d dequantise %7.2f us  %7.1f GB/s (%4.1f%% of 8 TB/s)  %s" %
+                  (M, K, b, us, row["dequant_GBps"], 100 * row["frac_of_peak"],
+                   " ".join("batch%s=%.1fus" % (k[13:], v) for k, v in row.items() if k.startswith("gemm_us"))),
+                  file=sys.stderr)
+        for c in copies:
+            c.close()
+    print(json.dumps(dict(metric="dequantise kernel GB/s (b/8 bytes read + 2 bytes written per weight) and "
+                                 "dequantise + dense FP16 GEMM latency", unit="GB/s", n_gpus=1, data="synthetic",
+                          rows=rows)))
+
+
 def decode_step(args, np, torch, B, inputs, dev):
     """Config 4: all 224 matrices of a 7B-shaped model resident, one bit-width per decode step.
 
@@ -103,6 +161,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 5],
                     help="benchmark configuration to run (default 2 = the headline workload)")
     ap.add_argument("--batch", type=int, default=1, help="batch size (exploration only; headline is 1)")
+    ap.add_argument("--large-batch", action="store_true",
+                    help="instead of the headline line: the dequantise kernel and the dequantise + dense GEMM "
+                         "path (batch 16..512) on the headline shapes; prints one JSON line")
     ap.add_argument("--decode-step", action="store_true",
                     help="instead of the headline line: the 7B-shaped decode step (32 layers x 7 matrices packed "
                          "once, a seeded sequence of per-step bit-widths); prints one JSON line with per-b latency")
@@ -124,6 +185,9 @@ def main():
     torch.cuda.set_device(0)
     if args.decode_step:
         decode_step(args, np, torch, B, inputs, dev)
+        return
+    if args.large_batch:
+        large_batch(args, np, torch, B, inputs, dev)
         return
     cfg = inputs.CONFIGS[args.config]
     shapes = cfg["shapes"]

@@ -112,6 +112,28 @@ ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int
                   void *stream);
 
 /*
+ * Dense binary16 weights of the b-bit model: w_dev[i*K + j] = C_b[i][ idx[i][j] >> (n-b) ], bit for
+ * bit the table entries (Section 6.2, "Matrix-Matrix Multiplication Performance": for large batches
+ * the engine dequantises with a separate kernel and uses a dense FP16 GEMM).
+ *   w_dev   device, M*K binary16 row-major, 16-byte aligned, caller-owned
+ * Asynchronous on `stream`; allocates nothing.
+ */
+ap_status ap_dequantize(const ap_matrix *h, int b, void *w_dev, void *stream);
+
+/*
+ * y = x * W_b^T for any batch >= 1 through the dequantise + dense GEMM path (the paper's route for
+ * batch above ~16): ap_dequantize into work_dev, then one FP16 GEMM with binary32 accumulation
+ * from rocBLAS, which is loaded on first use (AP_ERR_HIP if it cannot be loaded or fails).
+ *   x_dev     device, batch*K binary16 row-major;  y_dev  device, batch*M binary16 row-major
+ *   work_dev  device, >= ap_gemm_workspace_size bytes (M*K*2), 16-byte aligned, caller-owned
+ * The first call on a process creates the rocBLAS handle (that call allocates and is not
+ * capturable in a graph); later calls only enqueue work on `stream`.
+ */
+ap_status ap_gemm_workspace_size(const ap_matrix *h, size_t *bytes);
+ap_status ap_gemm(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int batch,
+                  void *work_dev, size_t work_bytes, void *stream);
+
+/*
  * Measurement aid, not part of the method: reads `bytes` (a multiple of 16384) of device memory
  * with the same instruction and access shape as the GEMV's slice loads (non-temporal 16-byte
  * loads, 1 KB contiguous per wave) and discards them.  Profiling counters of HBM traffic are

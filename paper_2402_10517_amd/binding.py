@@ -22,8 +22,8 @@ STATUS_NAMES = {0: "AP_OK", 1: "AP_ERR_INVALID_ARG", 2: "AP_ERR_SHAPE", 3: "AP_E
                 7: "AP_ERR_HIP"}
 
 EXPORTS = ["ap_packed_size", "ap_pack_host", "ap_unpack_host", "ap_blob_lut_entry",
-           "ap_read_extent", "ap_pack", "ap_attach", "ap_unpack", "ap_gemv", "ap_probe_read",
-           "ap_matrix_info",
+           "ap_read_extent", "ap_pack", "ap_attach", "ap_unpack", "ap_gemv", "ap_dequantize",
+           "ap_gemm_workspace_size", "ap_gemm", "ap_probe_read", "ap_matrix_info",
            "ap_free", "ap_strerror"]
 
 
@@ -49,6 +49,9 @@ def _load():
     L.ap_attach.argtypes = [vp, sz, vp, ctypes.POINTER(vp)]
     L.ap_unpack.argtypes = [vp, vp, vp]
     L.ap_gemv.argtypes = [vp, ci, vp, vp, ci, vp]
+    L.ap_dequantize.argtypes = [vp, ci, vp, vp]
+    L.ap_gemm_workspace_size.argtypes = [vp, psz]
+    L.ap_gemm.argtypes = [vp, ci, vp, vp, ci, vp, sz, vp]
     L.ap_probe_read.argtypes = [vp, sz, vp]
     L.ap_matrix_info.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci),
                                  ctypes.POINTER(cu)]
@@ -187,6 +190,31 @@ def ap_gemv(pm, b, x, y=None, stream=None):
         y = torch.empty((batch, pm.M), dtype=torch.float16, device=x.device)
     sp, _ = _stream_ptr(stream)
     _check(lib.ap_gemv(pm.handle, int(b), x.data_ptr(), y.data_ptr(), batch, sp), "ap_gemv")
+    return y
+
+
+def ap_dequantize(pm, b, w=None, stream=None):
+    """Dense (M, K) float16 device tensor of the b-bit model's weights."""
+    if w is None:
+        w = torch.empty((pm.M, pm.K), dtype=torch.float16, device=pm.buf.device)
+    sp, _ = _stream_ptr(stream)
+    _check(lib.ap_dequantize(pm.handle, int(b), w.data_ptr(), sp), "ap_dequantize")
+    return w
+
+
+def ap_gemm(pm, b, x, work=None, y=None, stream=None):
+    """Large-batch path: x (batch, K) float16 -> y (batch, M) float16 via dequantise + dense GEMM."""
+    assert x.dtype == torch.float16 and x.is_cuda and x.is_contiguous() and x.dim() == 2
+    batch = x.shape[0]
+    size = ctypes.c_size_t(0)
+    _check(lib.ap_gemm_workspace_size(pm.handle, ctypes.byref(size)), "ap_gemm_workspace_size")
+    if work is None:
+        work = torch.empty(size.value, dtype=torch.uint8, device=x.device)
+    if y is None:
+        y = torch.empty((batch, pm.M), dtype=torch.float16, device=x.device)
+    sp, _ = _stream_ptr(stream)
+    _check(lib.ap_gemm(pm.handle, int(b), x.data_ptr(), y.data_ptr(), batch, work.data_ptr(),
+                       work.numel(), sp), "ap_gemm")
     return y
 
 

@@ -6,6 +6,7 @@
 #include <new>
 #include <vector>
 
+#include "dense_gemm.h"
 #include "kernels.h"
 #include "pack.h"
 
@@ -139,6 +140,59 @@ extern "C" ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void 
     a.waves_per_group = h->waves_per_group;
     a.row_groups_per_wg = h->row_groups_per_wg;
     return launch_gemv(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+static ap_status fill_args(const ap_matrix *h, int b, GemvArgs *a)
+{
+    if (!handle_ok(h)) return AP_ERR_INVALID_ARG;
+    if (b < AP_MIN_BITS || b > h->hdr.n || !(h->hdr.lut_mask & (1u << b))) return AP_ERR_BITS;
+    a->slices = h->dev + h->hdr.slice_off;
+    a->slice_bytes = h->hdr.slice_bytes;
+    a->lut = reinterpret_cast<const uint16_t *>(h->dev + h->hdr.lut_off[b]);
+    a->x = nullptr;
+    a->y = nullptr;
+    a->M = h->hdr.M;
+    a->K = h->hdr.K;
+    a->b = b;
+    a->batch = 1;
+    a->waves_per_group = h->waves_per_group;
+    a->row_groups_per_wg = h->row_groups_per_wg;
+    return AP_OK;
+}
+
+extern "C" ap_status ap_dequantize(const ap_matrix *h, int b, void *w_dev, void *stream)
+{
+    GemvArgs a;
+    ap_status s = fill_args(h, b, &a);
+    if (s != AP_OK) return s;
+    if (!w_dev || reinterpret_cast<uintptr_t>(w_dev) % 16) return AP_ERR_INVALID_ARG;
+    a.y = static_cast<uint16_t *>(w_dev);
+    return launch_dequantize(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+extern "C" ap_status ap_gemm_workspace_size(const ap_matrix *h, size_t *bytes)
+{
+    if (!handle_ok(h) || !bytes) return AP_ERR_INVALID_ARG;
+    *bytes = (size_t)h->hdr.M * (size_t)h->hdr.K * 2;
+    return AP_OK;
+}
+
+extern "C" ap_status ap_gemm(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int batch,
+                             void *work_dev, size_t work_bytes, void *stream)
+{
+    GemvArgs a;
+    ap_status s = fill_args(h, b, &a);
+    if (s != AP_OK) return s;
+    if (!x_dev || !y_dev || !work_dev) return AP_ERR_INVALID_ARG;
+    if (batch < 1 || batch > (1 << 20)) return AP_ERR_BATCH;
+    if (reinterpret_cast<uintptr_t>(work_dev) % 16 || reinterpret_cast<uintptr_t>(x_dev) % 2 ||
+        reinterpret_cast<uintptr_t>(y_dev) % 2)
+        return AP_ERR_INVALID_ARG;
+    if (work_bytes < (size_t)a.M * (size_t)a.K * 2) return AP_ERR_BUFFER_TOO_SMALL;
+    a.y = static_cast<uint16_t *>(work_dev);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (launch_dequantize(a, st) != hipSuccess) return AP_ERR_HIP;
+    return dense_gemm_f16(work_dev, x_dev, y_dev, a.M, a.K, batch, st) ? AP_OK : AP_ERR_HIP;
 }
 
 extern "C" ap_status ap_probe_read(const void *dev_buf, size_t bytes, void *stream)

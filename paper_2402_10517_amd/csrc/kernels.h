@@ -20,6 +20,7 @@ struct GemvArgs {
 };
 
 hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream);
+hipError_t launch_dequantize(const GemvArgs &a, hipStream_t stream);
 hipError_t launch_probe_read(const void *dev_buf, size_t bytes, hipStream_t stream);
 
 } // namespace apgemv
