@@ -18,6 +18,7 @@ struct ap_matrix {
     uint8_t *dev;
     int waves_per_group;
     int row_groups_per_wg;
+    int mfma_min_batch;
 };
 static constexpr uint32_t kHandleTag = 0x41504d58u;
 
@@ -27,6 +28,11 @@ static bool handle_ok(const ap_matrix *h) { return h && h->tag == kHandleTag && 
 static int env_waves()
 {
     const char *e = std::getenv("APGEMV_WAVES");
+    return e ? std::atoi(e) : 0;
+}
+static int env_mfma_min_batch()
+{
+    const char *e = std::getenv("APGEMV_MFMA_MIN_BATCH");
     return e ? std::atoi(e) : 0;
 }
 static int env_row_groups()
@@ -72,6 +78,7 @@ extern "C" ap_status ap_pack(const uint8_t *idx_host, int M, int K, int n,
     h->dev = static_cast<uint8_t *>(dev_buf);
     h->waves_per_group = env_waves();
     h->row_groups_per_wg = env_row_groups();
+    h->mfma_min_batch = env_mfma_min_batch();
     *out = h;
     return AP_OK;
 }
@@ -94,6 +101,7 @@ extern "C" ap_status ap_attach(void *dev_buf, size_t dev_buf_bytes, void *stream
     h->dev = static_cast<uint8_t *>(dev_buf);
     h->waves_per_group = env_waves();
     h->row_groups_per_wg = env_row_groups();
+    h->mfma_min_batch = env_mfma_min_batch();
     *out = h;
     return AP_OK;
 }
@@ -139,6 +147,7 @@ extern "C" ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void 
     a.batch = batch;
     a.waves_per_group = h->waves_per_group;
     a.row_groups_per_wg = h->row_groups_per_wg;
+    a.mfma_min_batch = h->mfma_min_batch;
     return launch_gemv(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
@@ -157,6 +166,7 @@ static ap_status fill_args(const ap_matrix *h, int b, GemvArgs *a)
     a->batch = 1;
     a->waves_per_group = h->waves_per_group;
     a->row_groups_per_wg = h->row_groups_per_wg;
+    a->mfma_min_batch = h->mfma_min_batch;
     return AP_OK;
 }
 

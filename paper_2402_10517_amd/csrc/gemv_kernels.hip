@@ -174,12 +174,13 @@ __device__ __forceinline__ void stage_tables_load(StagedTable<B> &st, const uint
 // The LDS writes are unconditional as well (threads without a piece write a 16-byte dummy area
 // behind the tables): a conditional store would pull its load down into the branch, behind the
 // slice loads.
-template <int B>
+template <int B, int STRIDE = Table<B>::kRowBytes>
 __device__ __forceinline__ void stage_tables_store(const StagedTable<B> &st, uint8_t *tab, uint16_t *nat)
 {
     using T = Table<B>;
     constexpr int TB = T::kRowBytes;
-    constexpr int kDummy = kRowsPerGroup * TB; // byte offset of the dummy area inside tab
+    static_assert(STRIDE >= TB, "row stride in LDS");
+    constexpr int kDummy = kRowsPerGroup * STRIDE; // byte offset of the dummy area inside tab
     const int tid = threadIdx.x, nth = blockDim.x;
     if constexpr (B == 3) {
         // the 64-entry table of centroid pairs: pair index bit 2k is code bit k of the even slot,
@@ -193,20 +194,22 @@ __device__ __forceinline__ void stage_tables_store(const StagedTable<B> &st, uin
             const int a = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
             const int c = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
             const uint32_t v = (uint32_t)nat[r * 8 + a] | ((uint32_t)nat[r * 8 + c] << 16);
-            *reinterpret_cast<uint32_t *>(tab + r * TB + i6 * 4) = v;
+            *reinterpret_cast<uint32_t *>(tab + r * STRIDE + i6 * 4) = v;
         }
     } else if constexpr (B >= 6) {
-        constexpr int kChunks = kRowsPerGroup * TB / 16;
+        constexpr int kPerRow = TB / 16;
+        constexpr int kChunks = kRowsPerGroup * kPerRow;
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int i = tid + it * nth;
-            reinterpret_cast<u32x4 *>(tab)[i < kChunks ? i : kChunks] = st.v[it];
+            const int off = i < kChunks ? (i / kPerRow) * STRIDE + (i % kPerRow) * 16 : kDummy;
+            *reinterpret_cast<u32x4 *>(tab + off) = st.v[it];
         }
     } else {
         // spread the two entries of a dword to their dword-strided LDS addresses
         constexpr int kDwordsPerRow = (1 << B) / 2;
         const int r = tid / kDwordsPerRow, k = tid % kDwordsPerRow;
-        uint8_t *dst = tid < kRowsPerGroup * kDwordsPerRow ? tab + r * TB + T::stored_addr(2 * k) : tab + kDummy;
+        uint8_t *dst = tid < kRowsPerGroup * kDwordsPerRow ? tab + r * STRIDE + T::stored_addr(2 * k) : tab + kDummy;
         *reinterpret_cast<uint16_t *>(dst) = (uint16_t)st.v[0].x;
         *reinterpret_cast<uint16_t *>(dst + 4) = (uint16_t)(st.v[0].x >> 16);
     }
@@ -507,6 +510,242 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(1, 6))) vo
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Small-batch variant on the matrix cores (batch 3..8).  The paper's kernel runs batches on the
+// ordinary ALUs and slows down by up to 2x at batch 8 (Section 6.2; Appendix C.3); here the
+// multiply-accumulates of a batch go to v_mfma_f32_4x4x4_16B_f16, whose 16 independent 4x4x4
+// blocks fit the layout's groups of 4 rows: block = 4 adjacent lanes, lane q of a block supplies
+// A row q (4 consecutive weights of output row q) and B column q (the same 4 columns of batch row
+// q), and receives D column q (4 output rows x batch row q).  For that a lane owns ONE row of the
+// group and 4 chunks of the span (4 dword loads per slice instead of one 16-byte load), and
+// the 4 rows' tables sit 256 (b <= 7) or 512 bytes apart so that the row is part of the LDS
+// address.  Requires K % 128 == 0 (every block of 4 chunks is entirely inside or outside a span).
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// byte J of v (already masked to table-address bits) with the lane's table row in address bits 8..9
+template <int J> __device__ __forceinline__ uint32_t row_byte_addr(uint32_t v, uint32_t rowreg)
+{
+    return __builtin_amdgcn_perm(rowreg, v, 0x0c0c0400u | J);
+}
+
+// Tables of `ng` consecutive groups of 4 rows into LDS, row stride STRIDE (generic loop form).
+template <int B, int STRIDE>
+__device__ __forceinline__ void stage_tables_groups(uint8_t *tab, uint16_t *nat, const uint16_t *__restrict__ lut,
+                                                    int row0, int nrows, int ng)
+{
+    using T = Table<B>;
+    constexpr int TB = T::kRowBytes;
+    const int tid = threadIdx.x, nth = blockDim.x;
+    if constexpr (B == 3) {
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(lut + (size_t)row0 * 8);
+        for (int i = tid; i < ng * kRowsPerGroup * 4; i += nth)
+            reinterpret_cast<uint32_t *>(nat)[i] = (i >> 2) < nrows ? src[i] : 0u;
+        __syncthreads();
+        for (int i = tid; i < ng * kRowsPerGroup * 64; i += nth) {
+            const int r = i >> 6, i6 = i & 63;
+            const int a = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
+            const int c = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
+            const uint32_t v = (uint32_t)nat[r * 8 + a] | ((uint32_t)nat[r * 8 + c] << 16);
+            *reinterpret_cast<uint32_t *>(tab + r * STRIDE + i6 * 4) = v;
+        }
+    } else if constexpr (B >= 6) {
+        constexpr int kPerRow = TB / 16;
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(lut + ((size_t)row0 << B));
+        for (int i = tid; i < ng * kRowsPerGroup * kPerRow; i += nth) {
+            const int r = i / kPerRow;
+            *reinterpret_cast<u32x4 *>(tab + r * STRIDE + (i % kPerRow) * 16) = r < nrows ? src[i] : u32x4{0, 0, 0, 0};
+        }
+    } else {
+        constexpr int kDwordsPerRow = (1 << B) / 2;
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(lut + ((size_t)row0 << B));
+        for (int i = tid; i < ng * kRowsPerGroup * kDwordsPerRow; i += nth) {
+            const int r = i / kDwordsPerRow, k = i % kDwordsPerRow;
+            const uint32_t v = r < nrows ? src[i] : 0u;
+            uint8_t *dst = tab + r * STRIDE + T::stored_addr(2 * k);
+            *reinterpret_cast<uint16_t *>(dst) = (uint16_t)v;
+            *reinterpret_cast<uint16_t *>(dst + 4) = (uint16_t)(v >> 16);
+        }
+    }
+}
+
+// R = consecutive groups of 4 rows per workgroup: a lane's activations of a chunk are loaded once
+// and used for R groups (activation traffic through the caches drops R-fold; at batch 8 it is
+// otherwise 8 KB of activations per KB of 3-bit weights).
+template <int B, int NBH, int R>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 6))) void gemv_mfma_kernel(
+    const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
+    const uint16_t *__restrict__ x, uint16_t *__restrict__ y, int M, int K, int batch)
+{
+    using T = Table<B>;
+    constexpr int STRIDE = B == 8 ? 512 : 256;
+    constexpr int kGroupBytes = kRowsPerGroup * STRIDE;
+    __shared__ __attribute__((aligned(16))) uint8_t tab[R * kGroupBytes];
+    __shared__ __attribute__((aligned(16))) uint16_t nat[R * kRowsPerGroup * 8];
+    __shared__ float red[8][R][NBH][4][4][4]; // [wave][group][batch half][output row][DPP row][batch row in half]
+
+    const int lane = threadIdx.x & 63;
+    const int q = lane & 3;      // row of a group this lane dequantises; batch row (in a half) it feeds
+    const int quad = lane >> 2;  // block of the matrix instruction
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nwaves = blockDim.x >> 6;
+    const int groups = (M + kRowsPerGroup - 1) / kRowsPerGroup;
+    const int g0 = blockIdx.x * R;
+    const int ng = groups - g0 < R ? groups - g0 : R;
+    const int row0 = g0 * kRowsPerGroup;
+    const int nrows = M - row0 < ng * kRowsPerGroup ? M - row0 : ng * kRowsPerGroup;
+    const int chunks = K / kChunkSlots;
+    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
+
+    stage_tables_groups<B, STRIDE>(tab, nat, lut, row0, nrows, ng);
+    __syncthreads();
+
+    float4_t D[R][NBH];
+#pragma unroll
+    for (int rg = 0; rg < R; ++rg)
+#pragma unroll
+        for (int h = 0; h < NBH; ++h) D[rg][h] = float4_t{0.f, 0.f, 0.f, 0.f};
+    const uint32_t rowreg = (uint32_t)q;                  // B <= 7: row in address bits 8..9 via v_perm
+    const uint32_t rowbase = (uint32_t)q * (uint32_t)STRIDE;
+    const uint8_t *xrow[NBH];
+#pragma unroll
+    for (int h = 0; h < NBH; ++h) {
+        const int br = 4 * h + q < batch ? 4 * h + q : batch - 1; // rows past the batch repeat the last one
+        xrow[h] = reinterpret_cast<const uint8_t *>(x + (size_t)br * K);
+    }
+
+    // One span of 2048 columns: acc[rg][h] += partial products of this lane's block.
+    auto run_span = [&](float4_t (&acc)[R][NBH], int span, int nl, int nq, int cq) {
+        const uint8_t *sbase = slices + ((size_t)g0 * chunks + (size_t)span * kSpanLanes) * 16 + q * 4;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint32_t c = (uint32_t)(p * nq + cq); // chunk inside the span
+            u32x4 X[NBH][4];
+#pragma unroll
+            for (int h = 0; h < NBH; ++h)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    X[h][t] = *reinterpret_cast<const u32x4 *>(
+                        xrow[h] + ((size_t)span * kSpanCols + (size_t)(t * 8 * nl) + c * 8u) * 2);
+#pragma unroll
+            for (int rg = 0; rg < R; ++rg) {
+                if (rg >= ng) break;
+                const uint8_t *tg = tab + rg * kGroupBytes;
+                uint32_t Qw[B];
+#pragma unroll
+                for (int s = 0; s < B; ++s)
+                    Qw[s] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(
+                        sbase + (size_t)rg * chunks * 16 + (size_t)s * slice_bytes + c * 16u));
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    uint32_t P[4]; // packed centroid pairs of columns 2j, 2j+1 of run t
+                    if constexpr (T::kPair) {
+                        const int u = 2 * t;
+                        uint32_t v = bitsel(rotl_c(0x30303030u, u), Qw[1], Qw[2]);
+                        v = bitsel(rotl_c(0xC0C0C0C0u, u), Qw[0], v);
+                        v = rotr_v(v, u) & 0xFCFCFCFCu;
+                        P[0] = *reinterpret_cast<const uint32_t *>(tg + row_byte_addr<0>(v, rowreg));
+                        P[1] = *reinterpret_cast<const uint32_t *>(tg + row_byte_addr<1>(v, rowreg));
+                        P[2] = *reinterpret_cast<const uint32_t *>(tg + row_byte_addr<2>(v, rowreg));
+                        P[3] = *reinterpret_cast<const uint32_t *>(tg + row_byte_addr<3>(v, rowreg));
+                    } else {
+                        uint32_t a[2][4];
+#pragma unroll
+                        for (int hh = 0; hh < 2; ++hh) {
+                            const int u = 2 * t + hh;
+                            uint32_t v = Qw[B - 1];
+#pragma unroll
+                            for (int s = B - 2; s >= 0; --s)
+                                v = bitsel(rotl_c(0x01010101u, u + slice_rot(s)), Qw[s], v);
+                            v = rotr_v(v, u);
+                            if constexpr (B == 8) {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j)
+                                    a[hh][j] = (((v >> (8 * j)) & 0xFFu) << 1) | rowbase;
+                            } else {
+                                v &= T::addr_mask() * 0x01010101u;
+                                a[hh][0] = row_byte_addr<0>(v, rowreg);
+                                a[hh][1] = row_byte_addr<1>(v, rowreg);
+                                a[hh][2] = row_byte_addr<2>(v, rowreg);
+                                a[hh][3] = row_byte_addr<3>(v, rowreg);
+                            }
+                        }
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const uint32_t w0 = *reinterpret_cast<const uint16_t *>(tg + a[0][j]);
+                            const uint32_t w1 = *reinterpret_cast<const uint16_t *>(tg + a[1][j]);
+                            P[j] = w0 | (w1 << 16);
+                        }
+                    }
+#pragma unroll
+                    for (int kq = 0; kq < 2; ++kq) {
+                        const u32x2 aw = {P[2 * kq], P[2 * kq + 1]};
+#pragma unroll
+                        for (int h = 0; h < NBH; ++h) {
+                            const u32x2 bw = {X[h][t][2 * kq], X[h][t][2 * kq + 1]};
+                            acc[rg][h] = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4_t, aw),
+                                                                            __builtin_bit_cast(half4_t, bw),
+                                                                            acc[rg][h], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+    };
+
+    for (int span = wave; span < nspans; span += nwaves) {
+        const int rem = chunks - span * kSpanLanes;
+        const int nl = rem < kSpanLanes ? rem : kSpanLanes;
+        const int nq = nl >> 2; // blocks in use; block b owns chunks p*nq + b, p = 0..3, so that the
+                                // blocks' loads of one p are adjacent in memory
+        if (nq == kSpanLanes / 4) {
+            run_span(D, span, nl, nq, quad);
+        } else {
+            // ragged last span: blocks past its end run on repeated data and their sums are dropped
+            const bool active = quad < nq;
+            float4_t Ds[R][NBH];
+#pragma unroll
+            for (int rg = 0; rg < R; ++rg)
+#pragma unroll
+                for (int h = 0; h < NBH; ++h) Ds[rg][h] = float4_t{0.f, 0.f, 0.f, 0.f};
+            run_span(Ds, span, nl, nq, active ? quad : nq - 1);
+#pragma unroll
+            for (int rg = 0; rg < R; ++rg)
+#pragma unroll
+                for (int h = 0; h < NBH; ++h)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) D[rg][h][i] += active ? Ds[rg][h][i] : 0.f;
+        }
+    }
+
+    // D[rg][h][i] of lane (block, q): output row i of group rg, batch row 4h+q, summed over the block's
+    // columns.  Add the 4 blocks of a DPP row (lanes with equal q), then waves and DPP rows through LDS.
+#pragma unroll
+    for (int rg = 0; rg < R; ++rg)
+#pragma unroll
+        for (int h = 0; h < NBH; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float c = D[rg][h][i];
+                c += dpp_get<0x114>(c); // row_shr:4
+                c += dpp_get<0x118>(c); // row_shr:8
+                if ((lane & 15) >= 12) red[wave][rg][h][i][lane >> 4][q] = c;
+            }
+    __syncthreads();
+    for (int o = threadIdx.x; o < ng * NBH * 16; o += blockDim.x) {
+        const int rg = o / (NBH * 16), h = (o / 16) % NBH, i = (o >> 2) & 3, j = o & 3;
+        float s = 0.f;
+        for (int w = 0; w < nwaves; ++w)
+            for (int d = 0; d < 4; ++d) s += red[w][rg][h][i][d][j];
+        const int row = row0 + rg * kRowsPerGroup + i, br = 4 * h + j;
+        if (row < M && br < batch) {
+            const __half hv = __float2half_rn(s);
+            y[(size_t)br * M + row] = __builtin_bit_cast(uint16_t, hv);
+        }
+    }
+}
+
 template <int B, int NB>
 static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
 {
@@ -537,8 +776,36 @@ static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
+template <int B, int NBH> static hipError_t launch_mfma(const GemvArgs &a, hipStream_t stream)
+{
+    const int groups = padded_rows(a.M) / kRowsPerGroup;
+    const int chunks = a.K / kChunkSlots;
+    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
+    int nw = 8;
+    if (a.waves_per_group > 0 && a.waves_per_group < nw) nw = a.waves_per_group;
+    if (nw > nspans) nw = nspans;
+    int rg = a.row_groups_per_wg;
+    if (rg < 0) rg = groups >= 2048 ? 4 : 1;
+    if (rg >= 4)
+        hipLaunchKernelGGL((gemv_mfma_kernel<B, NBH, 4>), dim3((groups + 3) / 4), dim3(64 * nw), 0, stream,
+                           a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
+    else if (rg >= 2)
+        hipLaunchKernelGGL((gemv_mfma_kernel<B, NBH, 2>), dim3((groups + 1) / 2), dim3(64 * nw), 0, stream,
+                           a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
+    else
+        hipLaunchKernelGGL((gemv_mfma_kernel<B, NBH, 1>), dim3(groups), dim3(64 * nw), 0, stream, a.slices,
+                           a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
+    return hipGetLastError();
+}
+
 template <int B> static hipError_t launch_b(const GemvArgs &a, hipStream_t stream)
 {
+    // Batch 3..8 at b >= 6 goes to the matrix cores when the row length allows it: measured 7-18 %
+    // faster than the ALU kernels there, slower at b <= 5, where the four rows' small tables of a
+    // block share LDS banks (mfma_min_batch: tuning override; a negative value also lifts the b limit)
+    const int min_batch = a.mfma_min_batch > 0 ? a.mfma_min_batch : a.mfma_min_batch < 0 ? -a.mfma_min_batch : 3;
+    if (a.batch >= min_batch && a.K % 128 == 0 && (B >= 6 || a.mfma_min_batch < 0))
+        return a.batch <= 4 ? launch_mfma<B, 1>(a, stream) : launch_mfma<B, 2>(a, stream);
     if (a.batch == 1) return launch_one<B, 1>(a, stream);
     if (a.batch == 2) return launch_one<B, 2>(a, stream);
     if (a.batch <= 4) return launch_one<B, 4>(a, stream);

@@ -17,6 +17,7 @@ struct GemvArgs {
     int M, K, b, batch;
     int waves_per_group;   // 0 = choose from the shape
     int row_groups_per_wg; // -1 = choose from the shape; 1 = one group of 4 rows per workgroup
+    int mfma_min_batch;    // 0 = default (3); batches below it use the ALU kernels; 9 = never
 };
 
 hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream);

@@ -162,6 +162,22 @@ def test_several_row_groups_per_workgroup(B, monkeypatch, rg, batch):
         pm.close()
 
 
+@pytest.mark.parametrize("batch", [3, 4, 5, 8])
+def test_matrix_core_variant_for_every_bit_width(B, monkeypatch, batch):
+    # forced for every b (the dispatcher uses it for b >= 6 only): several spans, a ragged last span
+    # of 4-chunk blocks, rows not a multiple of 4 or 16, one and four row groups per workgroup
+    monkeypatch.setenv("APGEMV_MFMA_MIN_BATCH", "-3")
+    for rg in ("1", "4"):
+        monkeypatch.setenv("APGEMV_ROW_GROUPS", rg)
+        for (M, K) in [(37, 128), (70, 2048 + 640), (21, 3 * 2048 + 128)]:
+            idx, luts, x = inputs.make_case(19, M, K, batch=batch, sigma=0.01)
+            pm = B.ap_pack(idx, luts)
+            for b in ALL_BITS:
+                y = run_gemv(pm, b, x)
+                check_against_oracle(y, idx, luts[b], b, x)
+            pm.close()
+
+
 def test_dispatch_sequence_without_repacking_and_determinism(B, tiny):
     import torch
     idx, luts, x, pm = tiny
