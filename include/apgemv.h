@@ -112,6 +112,23 @@ ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int
                   void *stream);
 
 /*
+ * Several GEMVs of the same bit-width in ONE launch: y_i = W_i,b * x_i for i < count (1..8), e.g. the
+ * q/k/v or the gate/up projections of a decoder layer (Section 6.3 measures whole-model decoding,
+ * where the per-launch cost of 224 small GEMVs per token matters).  All matrices must have the same
+ * K and a table for b; M may differ; x_dev/y_dev may be shared or distinct per item (outputs must
+ * not overlap).  At batch 1 and 2 each output is bit-identical to the one ap_gemv produces (same
+ * kernel per row group); at larger batches ap_gemv may pick another variant with a different
+ * summation order, and both meet the same tolerance.  Same argument rules and error codes as
+ * ap_gemv; AP_ERR_SHAPE if the row lengths differ.
+ */
+typedef struct {
+    const ap_matrix *h;
+    const void *x_dev; /* batch*K binary16 */
+    void *y_dev;       /* batch*M_i binary16 */
+} ap_gemv_item;
+ap_status ap_gemv_multi(const ap_gemv_item *items, int count, int b, int batch, void *stream);
+
+/*
  * Dense binary16 weights of the b-bit model: w_dev[i*K + j] = C_b[i][ idx[i][j] >> (n-b) ], bit for
  * bit the table entries (Section 6.2, "Matrix-Matrix Multiplication Performance": for large batches
  * the engine dequantises with a separate kernel and uses a dense FP16 GEMM).

@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "AP_OK", 1: "AP_ERR_INVALID_ARG", 2: "AP_ERR_SHAPE", 3: "AP_E
                 7: "AP_ERR_HIP"}
 
 EXPORTS = ["ap_packed_size", "ap_pack_host", "ap_unpack_host", "ap_blob_lut_entry",
-           "ap_read_extent", "ap_pack", "ap_attach", "ap_unpack", "ap_gemv", "ap_dequantize",
+           "ap_read_extent", "ap_pack", "ap_attach", "ap_unpack", "ap_gemv", "ap_gemv_multi", "ap_dequantize",
            "ap_gemm_workspace_size", "ap_gemm", "ap_probe_read", "ap_matrix_info",
            "ap_free", "ap_strerror"]
 
@@ -49,6 +49,7 @@ def _load():
     L.ap_attach.argtypes = [vp, sz, vp, ctypes.POINTER(vp)]
     L.ap_unpack.argtypes = [vp, vp, vp]
     L.ap_gemv.argtypes = [vp, ci, vp, vp, ci, vp]
+    L.ap_gemv_multi.argtypes = [vp, ci, ci, ci, vp]
     L.ap_dequantize.argtypes = [vp, ci, vp, vp]
     L.ap_gemm_workspace_size.argtypes = [vp, psz]
     L.ap_gemm.argtypes = [vp, ci, vp, vp, ci, vp, sz, vp]
@@ -191,6 +192,29 @@ def ap_gemv(pm, b, x, y=None, stream=None):
     sp, _ = _stream_ptr(stream)
     _check(lib.ap_gemv(pm.handle, int(b), x.data_ptr(), y.data_ptr(), batch, sp), "ap_gemv")
     return y
+
+
+class GemvItem(ctypes.Structure):
+    _fields_ = [("h", ctypes.c_void_p), ("x_dev", ctypes.c_void_p), ("y_dev", ctypes.c_void_p)]
+
+
+def make_items(triples):
+    """[(PackedMatrix, x tensor, y tensor), ...] -> ctypes array for ap_gemv_multi."""
+    arr = (GemvItem * len(triples))()
+    for i, (pm, x, y) in enumerate(triples):
+        arr[i].h = pm.handle.value if isinstance(pm.handle, ctypes.c_void_p) else pm.handle
+        arr[i].x_dev = x.data_ptr()
+        arr[i].y_dev = y.data_ptr()
+    return arr
+
+
+def ap_gemv_multi(triples, b, stream=None):
+    """One launch for several matrices of equal K: triples = [(PackedMatrix, x, y), ...]; fills the y's."""
+    batch = 1 if triples[0][1].dim() == 1 else triples[0][1].shape[0]
+    arr = make_items(triples)
+    sp, _ = _stream_ptr(stream)
+    _check(lib.ap_gemv_multi(arr, len(triples), int(b), batch, sp), "ap_gemv_multi")
+    return [t[2] for t in triples]
 
 
 def ap_dequantize(pm, b, w=None, stream=None):

@@ -170,6 +170,36 @@ static ap_status fill_args(const ap_matrix *h, int b, GemvArgs *a)
     return AP_OK;
 }
 
+extern "C" ap_status ap_gemv_multi(const ap_gemv_item *items, int count, int b, int batch, void *stream)
+{
+    if (!items || count < 1 || count > kMaxMulti) return AP_ERR_INVALID_ARG;
+    if (batch < 1 || batch > AP_MAX_BATCH) return AP_ERR_BATCH;
+    MultiArgs m;
+    std::memset(&m, 0, sizeof(m));
+    int total = 0;
+    for (int i = 0; i < count; ++i) {
+        GemvArgs a;
+        ap_status s = fill_args(items[i].h, b, &a);
+        if (s != AP_OK) return s;
+        if (!items[i].x_dev || !items[i].y_dev) return AP_ERR_INVALID_ARG;
+        if (reinterpret_cast<uintptr_t>(items[i].x_dev) % 16 || reinterpret_cast<uintptr_t>(items[i].y_dev) % 2)
+            return AP_ERR_INVALID_ARG;
+        if (i > 0 && a.K != m.K) return AP_ERR_SHAPE;
+        m.K = a.K;
+        m.slices[i] = a.slices;
+        m.slice_bytes[i] = a.slice_bytes;
+        m.lut[i] = a.lut;
+        m.x[i] = static_cast<const uint16_t *>(items[i].x_dev);
+        m.y[i] = static_cast<uint16_t *>(items[i].y_dev);
+        m.M[i] = a.M;
+        m.group_begin[i] = total;
+        total += padded_rows(a.M) / kRowsPerGroup;
+    }
+    m.count = count;
+    m.batch = batch;
+    return launch_gemv_multi(m, b, total, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
 extern "C" ap_status ap_dequantize(const ap_matrix *h, int b, void *w_dev, void *stream)
 {
     GemvArgs a;

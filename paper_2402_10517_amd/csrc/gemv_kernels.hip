@@ -189,10 +189,12 @@ __device__ __forceinline__ void stage_tables_store(const StagedTable<B> &st, uin
                                                 : reinterpret_cast<uint32_t *>(tab + kDummy);
         *dst = st.v[0].x;
         __syncthreads();
-        for (int i = tid; i < kRowsPerGroup * 64; i += nth) {
-            const int r = i >> 6, i6 = i & 63;
-            const int a = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
-            const int c = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
+        // a thread's pair index is its lane (the block size is a multiple of 64): the two codes are
+        // formed once, the loop only walks the rows
+        const int i6 = tid & 63;
+        const int a = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
+        const int c = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
+        for (int r = tid >> 6; r < kRowsPerGroup; r += nth >> 6) {
             const uint32_t v = (uint32_t)nat[r * 8 + a] | ((uint32_t)nat[r * 8 + c] << 16);
             *reinterpret_cast<uint32_t *>(tab + r * STRIDE + i6 * 4) = v;
         }
@@ -299,12 +301,9 @@ __device__ __forceinline__ void compute_unit(const u32x4 (&Q)[B], const u32x4 (&
 // spans are loaded after the previous one is consumed (other waves of the CU cover the latency;
 // a second register set for prefetching cost more in occupancy than it gained).
 template <int B, int NB, int MAXT>
-__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 6))) void gemv_kernel(const uint8_t *__restrict__ slices,
-                                                     size_t slice_bytes,
-                                                     const uint16_t *__restrict__ lut,
-                                                     const uint16_t *__restrict__ x,
-                                                     uint16_t *__restrict__ y, int M, int K,
-                                                     int batch)
+__device__ __forceinline__ void gemv_group(const uint8_t *__restrict__ slices, size_t slice_bytes,
+                                           const uint16_t *__restrict__ lut, const uint16_t *__restrict__ x,
+                                           uint16_t *__restrict__ y, int M, int K, int batch, int g)
 {
     using T = Table<B>;
     constexpr int TB = T::kRowBytes;
@@ -312,7 +311,6 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 6))) vo
     __shared__ __attribute__((aligned(16))) uint16_t nat[kRowsPerGroup * 8];
     __shared__ float red[MAXT / 64][NB][4][kRowsPerGroup]; // [wave][batch row][DPP row][lane & 3]
 
-    const int g = blockIdx.x;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform, kept in an SGPR
     const int nwaves = blockDim.x >> 6;
@@ -387,6 +385,29 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 6))) vo
             y[(size_t)nb * M + row] = __builtin_bit_cast(uint16_t, h);
         }
     }
+}
+
+template <int B, int NB, int MAXT>
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 6))) void gemv_kernel(
+    const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
+    const uint16_t *__restrict__ x, uint16_t *__restrict__ y, int M, int K, int batch)
+{
+    gemv_group<B, NB, MAXT>(slices, slice_bytes, lut, x, y, M, K, batch, blockIdx.x);
+}
+
+// Several matrices with the same row length in one launch (the q/k/v or gate/up projections of
+// a decoder layer): workgroup -> (matrix, group of 4 rows) through the prefix sums of the group
+// counts.  Each matrix keeps its own activations and outputs; the work per group is that of
+// gemv_kernel, so results are bit-identical to separate calls that use it.
+template <int B, int NB, int MAXT>
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 6))) void gemv_multi_kernel(MultiArgs a)
+{
+    int m = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxMulti; ++i)
+        if (i < a.count && (int)blockIdx.x >= a.group_begin[i]) m = i;
+    gemv_group<B, NB, MAXT>(a.slices[m], a.slice_bytes[m], a.lut[m], a.x[m], a.y[m], a.M[m], a.K, a.batch,
+                            (int)blockIdx.x - a.group_begin[m]);
 }
 
 // Variant for matrices with many rows and for batches: one workgroup owns up to kMaxRowGroups
@@ -945,6 +966,37 @@ hipError_t launch_probe_read(const void *dev_buf, size_t bytes, hipStream_t stre
     hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
                        static_cast<const u32x4 *>(dev_buf), static_cast<uint32_t *>(nullptr));
     return hipGetLastError();
+}
+
+template <int B, int NB> static hipError_t launch_multi_one(const MultiArgs &a, int total_groups, hipStream_t stream)
+{
+    constexpr int kMaxWaves = NB <= 4 ? 8 : 4;
+    const int chunks = a.K / kChunkSlots;
+    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
+    const int nw = nspans < kMaxWaves ? nspans : kMaxWaves;
+    hipLaunchKernelGGL((gemv_multi_kernel<B, NB, 64 * kMaxWaves>), dim3(total_groups), dim3(64 * nw), 0, stream, a);
+    return hipGetLastError();
+}
+
+template <int B> static hipError_t launch_multi_b(const MultiArgs &a, int total_groups, hipStream_t stream)
+{
+    if (a.batch == 1) return launch_multi_one<B, 1>(a, total_groups, stream);
+    if (a.batch == 2) return launch_multi_one<B, 2>(a, total_groups, stream);
+    if (a.batch <= 4) return launch_multi_one<B, 4>(a, total_groups, stream);
+    return launch_multi_one<B, 8>(a, total_groups, stream);
+}
+
+hipError_t launch_gemv_multi(const MultiArgs &a, int b, int total_groups, hipStream_t stream)
+{
+    switch (b) {
+    case 3: return launch_multi_b<3>(a, total_groups, stream);
+    case 4: return launch_multi_b<4>(a, total_groups, stream);
+    case 5: return launch_multi_b<5>(a, total_groups, stream);
+    case 6: return launch_multi_b<6>(a, total_groups, stream);
+    case 7: return launch_multi_b<7>(a, total_groups, stream);
+    case 8: return launch_multi_b<8>(a, total_groups, stream);
+    }
+    return hipErrorInvalidValue;
 }
 
 // Bit-width dispatch: one stored matrix, the kernel and the table are chosen per call

@@ -20,7 +20,20 @@ struct GemvArgs {
     int mfma_min_batch;    // 0 = default (3); batches below it use the ALU kernels; 9 = never
 };
 
+constexpr int kMaxMulti = 8;
+struct MultiArgs { // passed by value as the kernel argument of a fused launch
+    const uint8_t *slices[kMaxMulti];
+    size_t slice_bytes[kMaxMulti];
+    const uint16_t *lut[kMaxMulti];
+    const uint16_t *x[kMaxMulti];
+    uint16_t *y[kMaxMulti];
+    int M[kMaxMulti];
+    int group_begin[kMaxMulti]; // first workgroup of matrix i
+    int count, K, batch;
+};
+
 hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream);
+hipError_t launch_gemv_multi(const MultiArgs &a, int b, int total_groups, hipStream_t stream);
 hipError_t launch_dequantize(const GemvArgs &a, hipStream_t stream);
 hipError_t launch_probe_read(const void *dev_buf, size_t bytes, hipStream_t stream);
 

@@ -166,6 +166,7 @@ def test_error_paths_before_any_device_work():
     assert L.ap_pack(idx.ctypes.data, M, K, 8, arr, fake_dev, 16, None, ctypes.byref(h)) == 5
     assert L.ap_pack(idx.ctypes.data, M, K, 8, arr, ctypes.c_void_p(0x10004), 1 << 20, None,
                      ctypes.byref(h)) == 1                                    # misaligned buffer
+    assert L.ap_gemv_multi(None, 1, 4, 1, None) == 1
     assert L.ap_dequantize(None, 4, fake_dev, None) == 1
     assert L.ap_gemm_workspace_size(None, ctypes.byref(sz)) == 1
     assert L.ap_gemm(None, 4, fake_dev, fake_dev, 32, fake_dev, 1 << 20, None) == 1

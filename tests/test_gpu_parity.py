@@ -178,6 +178,42 @@ def test_matrix_core_variant_for_every_bit_width(B, monkeypatch, batch):
             pm.close()
 
 
+@pytest.mark.parametrize("batch", [1, 2, 8])
+def test_fused_launch_equals_separate_calls(B, batch):
+    import torch
+    K = 2048 + 256
+    mats = []
+    for k, M in enumerate([64, 37, 130, 8]):
+        idx, luts, x = inputs.make_case(20, M, K, batch=batch, salt=k)
+        mats.append((idx, luts, x, B.ap_pack(idx, luts)))
+    shared_x = torch.from_numpy(mats[0][2]).cuda()
+    for b in ALL_BITS:
+        for count in (1, 3, 4):
+            triples, ys = [], []
+            for (idx, luts, x, pm) in mats[:count]:
+                y = torch.full((batch, pm.M), -3.0, dtype=torch.float16, device="cuda")
+                triples.append((pm, shared_x, y))
+            B.ap_gemv_multi(triples, b)
+            torch.cuda.synchronize()
+            for (idx, luts, x, pm), (_, _, y) in zip(mats[:count], triples):
+                sep = B.ap_gemv(pm, b, shared_x)
+                torch.cuda.synchronize()
+                if batch <= 2:   # same kernel as the single call: bit-identical
+                    assert np.array_equal(y.cpu().numpy().view(np.uint16), sep.cpu().numpy().view(np.uint16))
+                check_against_oracle(y.cpu().numpy(), idx, luts[b], b, mats[0][2])
+    # row lengths must agree
+    idx, luts, x = inputs.make_case(20, 16, 512, batch=batch)
+    other = B.ap_pack(idx, luts)
+    y0 = torch.empty((batch, 64), dtype=torch.float16, device="cuda")
+    y1 = torch.empty((batch, 16), dtype=torch.float16, device="cuda")
+    with pytest.raises(B.ApError) as e:
+        B.ap_gemv_multi([(mats[0][3], shared_x, y0), (other, shared_x, y1)], 4)
+    assert e.value.status == 2
+    for m in mats:
+        m[3].close()
+    other.close()
+
+
 def test_dispatch_sequence_without_repacking_and_determinism(B, tiny):
     import torch
     idx, luts, x, pm = tiny
