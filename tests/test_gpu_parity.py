@@ -214,6 +214,43 @@ def test_fused_launch_equals_separate_calls(B, batch):
     other.close()
 
 
+def test_graph_capture_and_replay_match_eager(B, tiny):
+    # ap_gemv and ap_gemv_multi allocate nothing and synchronise nothing, so a stream capture can
+    # record them; every replay (with eager work and synchronisations in between) must reproduce
+    # the eager result bit for bit
+    import torch
+    idx, luts, x, pm = tiny
+    xd = torch.from_numpy(x).cuda()
+    eager = {b: B.ap_gemv(pm, b, xd).clone() for b in ALL_BITS}
+    torch.cuda.synchronize()
+    ys = {b: torch.zeros((1, pm.M), dtype=torch.float16, device="cuda") for b in ALL_BITS}
+    ym = torch.zeros((1, pm.M), dtype=torch.float16, device="cuda")
+    cap = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(cap):
+        for b in ALL_BITS:                       # warm-up on the capture stream
+            B.ap_gemv(pm, b, xd, y=ys[b], stream=cap)
+        cap.synchronize()
+        with torch.cuda.graph(g, stream=cap):
+            for b in ALL_BITS:
+                B.ap_gemv(pm, b, xd, y=ys[b], stream=cap)
+            B.ap_gemv_multi([(pm, xd, ym)], 5, stream=cap)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for b in ALL_BITS:
+            ys[b].zero_()
+        ym.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for b in ALL_BITS:
+            assert torch.equal(ys[b], eager[b]), (rep, b)
+        assert torch.equal(ym, eager[5])
+        # eager work between replays
+        assert torch.equal(B.ap_gemv(pm, 4 + rep % 3, xd), eager[4 + rep % 3])
+        torch.cuda.synchronize()
+
+
 def test_dispatch_sequence_without_repacking_and_determinism(B, tiny):
     import torch
     idx, luts, x, pm = tiny
