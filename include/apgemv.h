@@ -151,6 +151,20 @@ ap_status ap_gemm(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int
                   void *work_dev, size_t work_bytes, void *stream);
 
 /*
+ * Host-only any-precision quantiser (no HIP call): incremental upscaling of Section 4.  Every output
+ * channel (row of w) is clustered on its own: a seed model of n_seed bits from a weighted 1-D k-means
+ * (weights = sens, the per-weight sensitivities; NULL = all ones), then for b = n_seed..n-1 every
+ * cluster is divided in two by a weighted 2-means and the new bit is appended at the end of the index.
+ *   w, sens    host, M*K binary32 row-major
+ *   idx_out    host, M*K bytes: the n-bit parent indices (idx >> (n-b) is the b-bit model's index)
+ *   luts_out[b] host, for n_seed <= b <= n: M * 2^b binary16 bit patterns (NULL = not wanted)
+ *   iters      Lloyd rounds per clustering (>= 1; 20 is plenty for one-dimensional data)
+ * The outputs are what ap_pack takes.  AP_ERR_BITS unless 1 <= n_seed <= n <= 8.
+ */
+ap_status ap_quantize(const float *w, const float *sens, int M, int K, int n_seed, int n, int iters,
+                      uint8_t *idx_out, uint16_t *const luts_out[9]);
+
+/*
  * Measurement aid, not part of the method: reads `bytes` (a multiple of 16384) of device memory
  * with the same instruction and access shape as the GEMV's slice loads (non-temporal 16-byte
  * loads, 1 KB contiguous per wave) and discards them.  Profiling counters of HBM traffic are

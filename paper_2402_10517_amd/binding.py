@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "AP_OK", 1: "AP_ERR_INVALID_ARG", 2: "AP_ERR_SHAPE", 3: "AP_E
 
 EXPORTS = ["ap_packed_size", "ap_pack_host", "ap_unpack_host", "ap_blob_lut_entry",
            "ap_read_extent", "ap_pack", "ap_attach", "ap_unpack", "ap_gemv", "ap_gemv_multi", "ap_dequantize",
-           "ap_gemm_workspace_size", "ap_gemm", "ap_probe_read", "ap_matrix_info",
+           "ap_gemm_workspace_size", "ap_gemm", "ap_quantize", "ap_probe_read", "ap_matrix_info",
            "ap_free", "ap_strerror"]
 
 
@@ -53,6 +53,7 @@ def _load():
     L.ap_dequantize.argtypes = [vp, ci, vp, vp]
     L.ap_gemm_workspace_size.argtypes = [vp, psz]
     L.ap_gemm.argtypes = [vp, ci, vp, vp, ci, vp, sz, vp]
+    L.ap_quantize.argtypes = [vp, vp, ci, ci, ci, ci, ci, vp, vp]
     L.ap_probe_read.argtypes = [vp, sz, vp]
     L.ap_matrix_info.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci),
                                  ctypes.POINTER(cu)]
@@ -240,6 +241,23 @@ def ap_gemm(pm, b, x, work=None, y=None, stream=None):
     _check(lib.ap_gemm(pm.handle, int(b), x.data_ptr(), y.data_ptr(), batch, work.data_ptr(),
                        work.numel(), sp), "ap_gemm")
     return y
+
+
+def ap_quantize(w, sens=None, n_seed=3, n=8, iters=20):
+    """Incremental-upscaling quantiser on the host: returns (idx uint8 (M, K), {b: float16 (M, 2**b)})."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    M, K = w.shape
+    if sens is not None:
+        sens = np.ascontiguousarray(sens, dtype=np.float32)
+        assert sens.shape == w.shape
+    idx = np.empty((M, K), dtype=np.uint8)
+    luts = {b: np.empty((M, 1 << b), dtype=np.uint16) for b in range(max(n_seed, 0), min(n, 8) + 1)}
+    arr = (ctypes.c_void_p * 9)()
+    for b, t in luts.items():
+        arr[b] = t.ctypes.data
+    _check(lib.ap_quantize(w.ctypes.data, None if sens is None else sens.ctypes.data, M, K, n_seed, n, iters,
+                           idx.ctypes.data, arr), "ap_quantize")
+    return idx, {b: t.view(np.float16) for b, t in luts.items()}
 
 
 def ap_gemv_raw(handle, b, x_ptr, y_ptr, batch, stream_ptr):

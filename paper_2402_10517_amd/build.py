@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libapgemv.so")
-SOURCES = ["gemv_kernels.hip", "api.cpp", "pack.cpp", "dense_gemm.cpp"]
+SOURCES = ["gemv_kernels.hip", "api.cpp", "pack.cpp", "dense_gemm.cpp", "quantize.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -83,11 +83,30 @@ template <class F> static void parallel_groups(int groups, F &&fn)
     for (auto &t : th) t.join();
 }
 
+// spread[v]: bit i of v (column offset i = 2j + parity inside a run of 8 columns) moved to bit
+// 8j + parity, the position of slot 8j + 2t + parity before the shift by 2t.
+static const uint32_t *spread_table()
+{
+    static uint32_t table[256];
+    static bool ready = [] {
+        for (int v = 0; v < 256; ++v) {
+            uint32_t w = 0;
+            for (int i = 0; i < 8; ++i)
+                if (v & (1 << i)) w |= 1u << (8 * (i >> 1) + (i & 1));
+            table[v] = w;
+        }
+        return true;
+    }();
+    (void)ready;
+    return table;
+}
+
 void pack_slices(const uint8_t *idx, const BlobHeader &h, uint8_t *blob)
 {
     const int M = h.M, K = h.K, n = h.n;
     const int chunks = K / kChunkSlots;
     const int groups = padded_rows(M) / kRowsPerGroup;
+    const uint32_t *spread = spread_table();
     parallel_groups(groups, [&](int g0, int g1) {
         for (int g = g0; g < g1; ++g) {
             for (int q = 0; q < chunks; ++q) {
@@ -98,10 +117,18 @@ void pack_slices(const uint8_t *idx, const BlobHeader &h, uint8_t *blob)
                     uint32_t plain[8] = {0, 0, 0, 0, 0, 0, 0, 0}; // plain[s]: bit of slot q at bit q
                     if (row < M) {
                         const uint8_t *src = idx + (size_t)row * K;
-                        for (int slot = 0; slot < kChunkSlots; ++slot) {
-                            const unsigned v = src[slot_column(span, nl, lane, slot)];
-                            for (int s = 0; s < n; ++s)
-                                plain[s] |= ((v >> (n - 1 - s)) & 1u) << slot;
+                        // a lane's slots are four runs of 8 consecutive columns (slot_column): take a
+                        // run as one 64-bit word, gather bit p of its 8 bytes into a byte with a
+                        // multiply, and spread that byte to the run's slot positions
+                        for (int t = 0; t < 4; ++t) {
+                            uint64_t x;
+                            std::memcpy(&x, src + slot_column(span, nl, lane, 2 * t), 8);
+                            for (int s = 0; s < n; ++s) {
+                                const int p = n - 1 - s;
+                                const uint64_t bits = (x >> p) & 0x0101010101010101ull;
+                                const uint32_t v = (uint32_t)((bits * 0x0102040810204080ull) >> 56);
+                                plain[s] |= spread[v] << (2 * t);
+                            }
                         }
                     }
                     for (int s = 0; s < n; ++s) {

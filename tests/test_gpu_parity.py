@@ -307,3 +307,24 @@ def test_attach_to_a_device_copy(B, tiny):
     for b in (3, 8):
         assert np.array_equal(run_gemv(pm2, b, x).view(np.uint16), run_gemv(pm, b, x).view(np.uint16))
     pm2.close()
+
+
+@pytest.mark.parametrize("batch", [1, 4])
+def test_quantised_model_end_to_end(B, batch):
+    # weights -> incremental upscaling (host) -> pack -> GEMV at every bit-width; the oracle takes
+    # the same indices and tables, and the b-bit result must approach the dense product as b grows
+    rng = np.random.default_rng([20240210, 31, batch])
+    M, K = 96, 2048 + 320
+    W = rng.standard_t(5, (M, K)).astype(np.float32) * 0.02
+    S = (rng.gamma(0.5, 1.0, (M, K)) + 1e-6).astype(np.float32)
+    idx, luts = B.ap_quantize(W, S, 3, 8, 15)
+    x = rng.normal(0, 1, (batch, K)).astype(np.float16)
+    pm = B.ap_pack(idx, luts)
+    dense = x.astype(np.float64) @ W.astype(np.float64).T
+    errs = []
+    for b in ALL_BITS:
+        y = run_gemv(pm, b, x)
+        check_against_oracle(y, idx, luts[b], b, x)
+        errs.append(float(np.sqrt(np.mean((y.astype(np.float64) - dense) ** 2))))
+    assert errs[-1] < errs[0] / 8 and errs[3] < errs[0]
+    pm.close()
