@@ -179,6 +179,10 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 5],
                     help="benchmark configuration to run (default 2 = the headline workload)")
     ap.add_argument("--batch", type=int, default=1, help="batch size (exploration only; headline is 1)")
+    ap.add_argument("--weights", choices=["uniform", "quantised"], default="uniform",
+                    help="uniform: uniform random indices and random tables (headline recipe); quantised: "
+                         "indices and tables from the incremental-upscaling quantiser on heavy-tailed weights "
+                         "(exploration: same bytes, non-uniform index statistics)")
     ap.add_argument("--large-batch", action="store_true",
                     help="instead of the headline line: the dequantise kernel and the dequantise + dense GEMM "
                          "path (batch 16..512) on the headline shapes; prints one JSON line")
@@ -216,6 +220,10 @@ def main():
     cases = []
     for (M, K) in shapes:
         idx, luts, x = inputs.make_case(args.config, M, K, batch=batch, sigma=cfg["sigma"])
+        if args.weights == "quantised":
+            W, S = inputs.make_dense_weights(args.config, M, K, sigma=cfg["sigma"])
+            idx, luts = B.ap_quantize(W, S, 3, 8, 10)
+            del W, S
         pm = B.ap_pack(idx, luts, device=dev)
         ncopies = max(2, min(COPIES, int(2.5e9 // pm.buf.numel())))
         copies = [pm] + [pm.clone() for _ in range(ncopies - 1)]
@@ -339,7 +347,8 @@ def main():
                     peak=HBM_PEAK_GBPS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBPS, 4),
                     bytes_per_launch=dom["bytes"] // dom["n"],
                     avg_launch_us=round(dom["us"] / dom["n"], 3),
-                    traffic=MEASURED_TRAFFIC_BYTES.get(dom_b) if args.config == 2 and batch == 1 else None)
+                    traffic=MEASURED_TRAFFIC_BYTES.get(dom_b)
+                    if args.config == 2 and batch == 1 and args.weights == "uniform" else None)
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload ----------------
     cpu = None
@@ -366,8 +375,9 @@ def main():
                vs_baseline=None, dtype="f16 tables and activations, f32 accumulate", data="synthetic",
                config=dict(workload=("configs[1]: Llama-2-7B linears 4096x4096, 11008x4096, 4096x11008; "
                                      "8-bit parent, b=3..8, batch 1; one step = 18 ap_gemv calls")
-                           if args.config == 2 and batch == 1 else
-                           "exploration: config %d (%s) shapes %s, batch %d" % (args.config, cfg["name"], shapes, batch),
+                           if args.config == 2 and batch == 1 and args.weights == "uniform" else
+                           "exploration: config %d (%s) shapes %s, batch %d, %s weights"
+                           % (args.config, cfg["name"], shapes, batch, args.weights),
                            calls_per_step=len(bits) * len(cases), bytes_per_step=step_bytes,
                            device_copies=COPIES, launch="hip-graph" if graphs is not None else "python-loop"),
                frac_of_hbm_peak=round(value / HBM_PEAK_GBPS, 4), us_per_call=round(ms_per_step * 1e3 / (len(bits) * len(cases)), 3),

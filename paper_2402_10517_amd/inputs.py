@@ -42,6 +42,16 @@ def make_case(config_id, M, K, batch=1, sigma=0.02, n=8, bit_widths=range(3, 9),
     return idx, luts, x
 
 
+def make_dense_weights(config_id, M, K, sigma=0.02, salt=0):
+    """Draw (W, S) for the quantiser: W (M, K) float32 heavy-tailed around 0 (Student t, 5 degrees of
+    freedom, scaled to sigma: LLM weight rows have a few large outliers), S (M, K) float32 positive,
+    skewed per-weight sensitivities (gamma, shape 0.5), standing in for the calibration gradients."""
+    rng = np.random.default_rng([BASE_SEED, config_id, M, K, salt, 1])
+    W = (rng.standard_t(5, size=(M, K)) * sigma).astype(np.float32)
+    S = (rng.gamma(0.5, 1.0, size=(M, K)) + 1e-6).astype(np.float32)
+    return W, S
+
+
 def decode_bit_sequence(steps=64):
     """Seeded per-step bit-widths of the decode-step configuration (config 4)."""
     rng = np.random.default_rng([BASE_SEED, 4])
