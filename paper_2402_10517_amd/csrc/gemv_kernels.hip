@@ -217,6 +217,66 @@ __device__ __forceinline__ void stage_tables_store(const StagedTable<B> &st, uin
     }
 }
 
+// Slice (0 = most significant) whose bits sit at rotation p among the first B slices, or -1.
+__device__ constexpr int slice_with_rot(int B, int p)
+{
+    for (int s = 0; s < B; ++s)
+        if (slice_rot(s) == p) return s;
+    return -1;
+}
+
+// Index formation for one row (Section 5.2 step 2; Section 5.3 "Efficient Bit-transpose"): turns the
+// row's B slice words into eight words W[u], u = 0..7, whose byte j holds the index of slot 8j + u
+// with the bit of slice s at byte bit slice_rot(s) (other byte bits are unspecified).  In pair mode
+// (B = 3) only even u are formed and byte bits 2..7 hold the interleaved indices of slots u, u + 1.
+//
+// Bits never move until the final rotate: slice s stores slot q at word bit q + slice_rot(s), so the
+// bits wanted for class u sit at word bits 8j + u + slice_rot(s).  The selects are shared between
+// classes as a three-level tree over the rotation value: level 1 joins rotations {2a, 2a+1} for the
+// classes u mod 2 (the two sources occupy alternating bits), level 2 joins {4c..4c+3} for u mod 4,
+// level 3 joins all eight for each u.  8 slices cost 8 + 8 + 8 selects and 7 rotates per 32 weights
+// instead of 8 x 7 selects; absent rotations (B < 8) drop their selects.
+template <int B>
+__device__ __forceinline__ void merge_row(const u32x4 (&Q)[B], int r, uint32_t (&W)[8])
+{
+    constexpr bool kPair = Table<B>::kPair;
+    constexpr int kStep = kPair ? 2 : 1;
+    uint32_t L1[4][2];
+    bool has1[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int lo = slice_with_rot(B, 2 * a), hi = slice_with_rot(B, 2 * a + 1);
+        has1[a] = lo >= 0 || hi >= 0;
+#pragma unroll
+        for (int c = 0; c < 2; c += kStep) {
+            if (lo >= 0 && hi >= 0) L1[a][c] = bitsel(rotl_c(0x55555555u, c), Q[lo < 0 ? 0 : lo][r], Q[hi < 0 ? 0 : hi][r]);
+            else if (lo >= 0) L1[a][c] = Q[lo < 0 ? 0 : lo][r];
+            else if (hi >= 0) L1[a][c] = Q[hi < 0 ? 0 : hi][r];
+            else L1[a][c] = 0;
+        }
+    }
+    uint32_t L2[2][4];
+    bool has2[2];
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2) {
+        has2[c2] = has1[2 * c2] || has1[2 * c2 + 1];
+#pragma unroll
+        for (int cls = 0; cls < 4; cls += kStep) {
+            const uint32_t lo = L1[2 * c2][cls & 1], hi = L1[2 * c2 + 1][cls & 1];
+            if (has1[2 * c2] && has1[2 * c2 + 1]) L2[c2][cls] = bitsel(rotl_c(0x33333333u, cls), lo, hi);
+            else L2[c2][cls] = has1[2 * c2] ? lo : hi;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; u += kStep) {
+        const uint32_t lo = L2[0][u & 3], hi = L2[1][u & 3];
+        uint32_t v;
+        if (has2[0] && has2[1]) v = bitsel(rotl_c(0x0F0F0F0Fu, u), lo, hi);
+        else v = has2[0] ? lo : hi;
+        W[u] = rotr_v(v, u);
+    }
+}
+
 // Index formation, table lookup and multiply-accumulate for the lane's 32 slots of 4 rows
 // (Section 5.2 steps 2-5).
 template <int B, int NB>
@@ -230,13 +290,12 @@ __device__ __forceinline__ void compute_unit(const u32x4 (&Q)[B], const u32x4 (&
 #pragma unroll
     for (int r = 0; r < kRowsPerGroup; ++r) {
         const uint8_t *trow = tab + r * TB;
+        uint32_t W[8];
+        merge_row<B>(Q, r, W);
         if constexpr (T::kPair) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const int u = 2 * t;
-                uint32_t v = bitsel(rotl_c(0x30303030u, u), Q[1][r], Q[2][r]);
-                v = bitsel(rotl_c(0xC0C0C0C0u, u), Q[0][r], v);
-                v = rotr_v(v, u);
+                const uint32_t v = W[2 * t];
                 const uint32_t a4[4] = {byte_and<0>(v, 0xFCu), byte_and<1>(v, 0xFCu), byte_and<2>(v, 0xFCu),
                                         byte_and<3>(v, 0xFCu)};
 #pragma unroll
@@ -259,12 +318,7 @@ __device__ __forceinline__ void compute_unit(const u32x4 (&Q)[B], const u32x4 (&
                 uint32_t a[2][4];
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    const int u = 2 * t + h;
-                    uint32_t v = Q[B - 1][r];
-#pragma unroll
-                    for (int s = B - 2; s >= 0; --s)
-                        v = bitsel(rotl_c(0x01010101u, u + slice_rot(s)), Q[s][r], v);
-                    v = rotr_v(v, u);
+                    const uint32_t v = W[2 * t + h];
                     a[h][0] = byte_to_addr<B, 0>(v, T::addr_mask(), one);
                     a[h][1] = byte_to_addr<B, 1>(v, T::addr_mask(), one);
                     a[h][2] = byte_to_addr<B, 2>(v, T::addr_mask(), one);
@@ -388,7 +442,7 @@ __device__ __forceinline__ void gemv_group(const uint8_t *__restrict__ slices, s
 }
 
 template <int B, int NB, int MAXT>
-__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 6))) void gemv_kernel(
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, (B <= 4 && NB == 1) ? 8 : 6))) void gemv_kernel(
     const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
     const uint16_t *__restrict__ x, uint16_t *__restrict__ y, int M, int K, int batch)
 {
