@@ -237,7 +237,7 @@ __device__ constexpr int slice_with_rot(int B, int p)
 // level 3 joins all eight for each u.  8 slices cost 8 + 8 + 8 selects and 7 rotates per 32 weights
 // instead of 8 x 7 selects; absent rotations (B < 8) drop their selects.
 template <int B>
-__device__ __forceinline__ void merge_row(const u32x4 (&Q)[B], int r, uint32_t (&W)[8])
+__device__ __forceinline__ void merge_words(const uint32_t (&q)[B], uint32_t (&W)[8])
 {
     constexpr bool kPair = Table<B>::kPair;
     constexpr int kStep = kPair ? 2 : 1;
@@ -249,9 +249,9 @@ __device__ __forceinline__ void merge_row(const u32x4 (&Q)[B], int r, uint32_t (
         has1[a] = lo >= 0 || hi >= 0;
 #pragma unroll
         for (int c = 0; c < 2; c += kStep) {
-            if (lo >= 0 && hi >= 0) L1[a][c] = bitsel(rotl_c(0x55555555u, c), Q[lo < 0 ? 0 : lo][r], Q[hi < 0 ? 0 : hi][r]);
-            else if (lo >= 0) L1[a][c] = Q[lo < 0 ? 0 : lo][r];
-            else if (hi >= 0) L1[a][c] = Q[hi < 0 ? 0 : hi][r];
+            if (lo >= 0 && hi >= 0) L1[a][c] = bitsel(rotl_c(0x55555555u, c), q[lo < 0 ? 0 : lo], q[hi < 0 ? 0 : hi]);
+            else if (lo >= 0) L1[a][c] = q[lo < 0 ? 0 : lo];
+            else if (hi >= 0) L1[a][c] = q[hi < 0 ? 0 : hi];
             else L1[a][c] = 0;
         }
     }
@@ -275,6 +275,14 @@ __device__ __forceinline__ void merge_row(const u32x4 (&Q)[B], int r, uint32_t (
         else v = has2[0] ? lo : hi;
         W[u] = rotr_v(v, u);
     }
+}
+template <int B>
+__device__ __forceinline__ void merge_row(const u32x4 (&Q)[B], int r, uint32_t (&W)[8])
+{
+    uint32_t q[B];
+#pragma unroll
+    for (int s = 0; s < B; ++s) q[s] = Q[s][r];
+    merge_words<B>(q, W);
 }
 
 // Index formation, table lookup and multiply-accumulate for the lane's 32 slots of 4 rows
@@ -712,14 +720,13 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 6))) voi
                 for (int s = 0; s < B; ++s)
                     Qw[s] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(
                         sbase + (size_t)rg * chunks * 16 + (size_t)s * slice_bytes + c * 16u));
+                uint32_t W[8];
+                merge_words<B>(Qw, W);
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     uint32_t P[4]; // packed centroid pairs of columns 2j, 2j+1 of run t
                     if constexpr (T::kPair) {
-                        const int u = 2 * t;
-                        uint32_t v = bitsel(rotl_c(0x30303030u, u), Qw[1], Qw[2]);
-                        v = bitsel(rotl_c(0xC0C0C0C0u, u), Qw[0], v);
-                        v = rotr_v(v, u) & 0xFCFCFCFCu;
+                        const uint32_t v = W[2 * t] & 0xFCFCFCFCu;
                         P[0] = *reinterpret_cast<const uint32_t *>(tg + row_byte_addr<0>(v, rowreg));
                         P[1] = *reinterpret_cast<const uint32_t *>(tg + row_byte_addr<1>(v, rowreg));
                         P[2] = *reinterpret_cast<const uint32_t *>(tg + row_byte_addr<2>(v, rowreg));
@@ -728,12 +735,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 6))) voi
                         uint32_t a[2][4];
 #pragma unroll
                         for (int hh = 0; hh < 2; ++hh) {
-                            const int u = 2 * t + hh;
-                            uint32_t v = Qw[B - 1];
-#pragma unroll
-                            for (int s = B - 2; s >= 0; --s)
-                                v = bitsel(rotl_c(0x01010101u, u + slice_rot(s)), Qw[s], v);
-                            v = rotr_v(v, u);
+                            uint32_t v = W[2 * t + hh];
                             if constexpr (B == 8) {
 #pragma unroll
                                 for (int j = 0; j < 4; ++j)
@@ -929,13 +931,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 6))) voi
         for (int r = 0; r < kRowsPerGroup; ++r) {
             const uint8_t *trow = tab + r * TB;
             u32x4 out[4]; // out[t][j] = columns 2j, 2j+1 of run t
+            uint32_t W[8];
+            merge_row<B>(Q, r, W);
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 if constexpr (T::kPair) {
-                    const int u = 2 * t;
-                    uint32_t v = bitsel(rotl_c(0x30303030u, u), Q[1][r], Q[2][r]);
-                    v = bitsel(rotl_c(0xC0C0C0C0u, u), Q[0][r], v);
-                    v = rotr_v(v, u);
+                    const uint32_t v = W[2 * t];
                     out[t][0] = *reinterpret_cast<const uint32_t *>(trow + byte_and<0>(v, 0xFCu));
                     out[t][1] = *reinterpret_cast<const uint32_t *>(trow + byte_and<1>(v, 0xFCu));
                     out[t][2] = *reinterpret_cast<const uint32_t *>(trow + byte_and<2>(v, 0xFCu));
@@ -944,12 +945,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 6))) voi
                     uint32_t a[2][4];
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
-                        const int u = 2 * t + h;
-                        uint32_t v = Q[B - 1][r];
-#pragma unroll
-                        for (int s = B - 2; s >= 0; --s)
-                            v = bitsel(rotl_c(0x01010101u, u + slice_rot(s)), Q[s][r], v);
-                        v = rotr_v(v, u);
+                        const uint32_t v = W[2 * t + h];
                         a[h][0] = byte_to_addr<B, 0>(v, T::addr_mask(), one);
                         a[h][1] = byte_to_addr<B, 1>(v, T::addr_mask(), one);
                         a[h][2] = byte_to_addr<B, 2>(v, T::addr_mask(), one);
