@@ -19,6 +19,7 @@ struct ap_matrix {
     int waves_per_group;
     int row_groups_per_wg;
     int mfma_min_batch;
+    int variant;
 };
 static constexpr uint32_t kHandleTag = 0x41504d58u;
 
@@ -33,6 +34,11 @@ static int env_waves()
 static int env_mfma_min_batch()
 {
     const char *e = std::getenv("APGEMV_MFMA_MIN_BATCH");
+    return e ? std::atoi(e) : 0;
+}
+static int env_variant()
+{
+    const char *e = std::getenv("APGEMV_VARIANT");
     return e ? std::atoi(e) : 0;
 }
 static int env_row_groups()
@@ -79,6 +85,7 @@ extern "C" ap_status ap_pack(const uint8_t *idx_host, int M, int K, int n,
     h->waves_per_group = env_waves();
     h->row_groups_per_wg = env_row_groups();
     h->mfma_min_batch = env_mfma_min_batch();
+    h->variant = env_variant();
     *out = h;
     return AP_OK;
 }
@@ -102,6 +109,7 @@ extern "C" ap_status ap_attach(void *dev_buf, size_t dev_buf_bytes, void *stream
     h->waves_per_group = env_waves();
     h->row_groups_per_wg = env_row_groups();
     h->mfma_min_batch = env_mfma_min_batch();
+    h->variant = env_variant();
     *out = h;
     return AP_OK;
 }
@@ -148,6 +156,7 @@ extern "C" ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void 
     a.waves_per_group = h->waves_per_group;
     a.row_groups_per_wg = h->row_groups_per_wg;
     a.mfma_min_batch = h->mfma_min_batch;
+    a.variant = h->variant;
     return launch_gemv(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
@@ -167,6 +176,7 @@ static ap_status fill_args(const ap_matrix *h, int b, GemvArgs *a)
     a->waves_per_group = h->waves_per_group;
     a->row_groups_per_wg = h->row_groups_per_wg;
     a->mfma_min_batch = h->mfma_min_batch;
+    a->variant = h->variant;
     return AP_OK;
 }
 

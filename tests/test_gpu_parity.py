@@ -178,6 +178,23 @@ def test_matrix_core_variant_for_every_bit_width(B, monkeypatch, batch):
             pm.close()
 
 
+@pytest.mark.parametrize("batch", [2, 3, 4, 5, 7, 8])
+def test_matrix_core_variant_with_in_block_exchange(B, monkeypatch, batch):
+    # forced for every b and batch >= 2: one span, several spans with a ragged last span of 4-chunk
+    # blocks, more spans than waves (a wave takes two spans), rows not a multiple of 4
+    # one, two and four row groups per workgroup (the last two reuse the activations of a span)
+    monkeypatch.setenv("APGEMV_VARIANT", "3")
+    for rg in ("1", "2", "4"):
+        monkeypatch.setenv("APGEMV_ROW_GROUPS", rg)
+        for (M, K) in [(37, 128), (70, 2048 + 640), (21, 3 * 2048 + 128), (9, 9 * 2048 + 256)]:
+            idx, luts, x = inputs.make_case(21, M, K, batch=batch, sigma=0.01)
+            pm = B.ap_pack(idx, luts)
+            for b in ALL_BITS:
+                y = run_gemv(pm, b, x)
+                check_against_oracle(y, idx, luts[b], b, x)
+            pm.close()
+
+
 @pytest.mark.parametrize("batch", [1, 2, 8])
 def test_fused_launch_equals_separate_calls(B, batch):
     import torch
