@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0
 # FETCH_SIZE and WRITE_SIZE from two `rocprofv3 --pmc` runs of this script, each scaled by what the
 # counter reads for a plain transfer of known size (ap_probe_read for reads: factor 1.9993;
 # the runtime's buffer copy for writes: factor 0.4965).  Source: profiles/gemv_config2_hbm_traffic.txt
-MEASURED_TRAFFIC_BYTES = {3: 13768788, 4: 18264593, 5: 22936475, 6: 27811037, 7: 33090957, 8: 39179552}
+MEASURED_TRAFFIC_BYTES = {3: 13773926, 4: 18266645, 5: 22924189, 6: 27796687, 7: 33070470, 8: 39167242}
 COPIES = 7      # device copies of every packed matrix (rotation period)
 
 
