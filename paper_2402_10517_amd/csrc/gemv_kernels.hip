@@ -1052,10 +1052,10 @@ static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
     int nw = kMaxWaves;
     if (a.waves_per_group > 0 && a.waves_per_group < nw) nw = a.waves_per_group;
     if (nw > nspans) nw = nspans;
-    // several row groups per workgroup when every span has its own wave and there are enough
-    // groups to keep the device full
+    // several row groups per workgroup at batch 5..8 when every span has its own wave and there are
+    // enough groups to keep the device full (at batch 2..4 the plain kernel measured faster)
     int rg = a.row_groups_per_wg;
-    if (rg < 0) rg = (nspans <= kMaxWaves && groups >= 2048 && NB >= 2) ? kMaxRowGroups : 1;
+    if (rg < 0) rg = (nspans <= kMaxWaves && groups >= 2048 && NB >= 8) ? kMaxRowGroups : 1;
     if (rg > kMaxRowGroups) rg = kMaxRowGroups;
     if (rg > 1 && nspans <= kMaxWaves) {
         hipLaunchKernelGGL((gemv_rows_kernel<B, NB, kMaxThreads>), dim3((groups + rg - 1) / rg),
@@ -1095,14 +1095,25 @@ template <int B> static hipError_t launch_b(const GemvArgs &a, hipStream_t strea
     // Batch 3..8 at b >= 6 goes to the matrix cores when the row length allows it: measured 7-18 %
     // faster than the ALU kernels there, slower at b <= 5, where the four rows' small tables of a
     // block share LDS banks (mfma_min_batch: tuning override; a negative value also lifts the b limit)
-    // Batch >= 2 with enough groups of rows to share a span's activations between four of them goes
-    // to the matrix cores with the in-wave exchange: measured faster than the ALU kernels at batch
-    // 5..8 for every b (up to 24 % at b <= 5) and at batch 2..4 for b = 4..7; level or slower at
-    // b = 3 and b = 8 there.  variant: 1 = never, 3 = whenever the shape allows (tuning override).
+    // Which kernel for batch >= 2 was settled by measurement on the 70B shapes (8192x8192, 28672x8192,
+    // 8192x28672; all b):
+    //  * batch 2: the plain kernel (one group of rows per workgroup) wins everywhere;
+    //  * batch 5..8 with >= 2048 groups of rows: the matrix-core kernel with in-wave exchange, every b
+    //    (up to 24 % faster than the ALU kernels at b <= 5, level at b = 8);
+    //  * batch 3..4: that kernel for b >= 6 and, on the tallest matrices (>= 4096 groups), for b = 4, 5,
+    //    when every span has its own wave; b = 3 and short matrices stay on the plain kernel, long
+    //    rows at b >= 6 on the first matrix-core kernel.
+    // variant: 1 = never the in-wave-exchange kernel, 3 = whenever the shape allows (tuning overrides).
     if (a.batch >= 2 && a.K % 128 == 0 && a.variant != 1) {
         const int groups = padded_rows(a.M) / kRowsPerGroup;
-        const bool pays = groups >= 2048 && a.row_groups_per_wg < 0 && (a.batch >= 5 || (B >= 4 && B <= 7));
-        if (a.variant == 3 || (pays && a.mfma_min_batch == 0))
+        const int nspans = (a.K / kChunkSlots + kSpanLanes - 1) / kSpanLanes;
+        const bool one_wave_per_span = nspans <= 8;
+        bool pays = false;
+        if (groups >= 2048 && a.row_groups_per_wg < 0 && a.mfma_min_batch == 0) {
+            if (a.batch >= 5) pays = true;
+            else if (a.batch >= 3 && one_wave_per_span) pays = B >= 6 || (B >= 4 && groups >= 4096);
+        }
+        if (a.variant == 3 || pays)
             return a.batch <= 4 ? launch_xmfma<B, 1>(a, stream) : launch_xmfma<B, 2>(a, stream);
     }
     const int min_batch = a.mfma_min_batch > 0 ? a.mfma_min_batch : a.mfma_min_batch < 0 ? -a.mfma_min_batch : 3;
