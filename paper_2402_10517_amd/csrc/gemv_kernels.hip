@@ -5,8 +5,9 @@
 // table indices, fetch centroids from the table rows staged in LDS, multiply-accumulate, reduce
 // over the lanes that share an output channel.  How each step is done differs from the paper's
 // kernel, which was written for 32-wide warps:
-//   * index formation needs no bit transpose: the slices are stored pre-rotated (layout.h), so a
-//     word of four table indices is (b-1) bit-selects with constant masks and one rotate;
+//   * index formation needs no bit transpose: the slices are stored pre-rotated (layout.h), so the
+//     eight words of four table indices each come out of a shared three-level tree of bit-selects
+//     with constant masks (24 selects per 32 weights at 8 bits) and one rotate per word;
 //   * b = 3 looks two weights up at once in a 64-entry table of centroid pairs and feeds the
 //     pair to one packed dot product (Section 5.3 "Merging Table Lookups");
 //   * a lane keeps its 32 activations in registers for 4 output rows;
@@ -93,11 +94,6 @@ template <int B> struct Table {
     }
 };
 
-template <int ctrl, int row_mask> __device__ __forceinline__ float dpp_add(float v)
-{
-    int t = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, row_mask, 0xf, false);
-    return v + __builtin_bit_cast(float, t);
-}
 template <int ctrl> __device__ __forceinline__ float dpp_get(float v)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true));

@@ -19,7 +19,8 @@
 //  * In slice s the bit of slot q sits at bit position (q + slice_rot(s)) mod 32 of the word.  With
 //    these rotations, the word for the four slots {8j+u, j=0..3} of one row is obtained by
 //    bit-selects with constant masks (no shifts) followed by one rotate right by u: byte j then
-//    holds slice s of slot 8j+u at bit slice_rot(s).  Because slice_rot(0..2) are even (6,4,2) and slot
+//    holds slice s of slot 8j+u at bit slice_rot(s).  Because the rotations 0..7 are all distinct,
+//    the selects of the eight words can share a tree over the rotation value (pairs, quads, all).  Because slice_rot(0..2) are even (6,4,2) and slot
 //    8j+u+1 sits one position higher, the same select for u even yields, at byte bits 2..7, the
 //    six bits of the slot pair (u, u+1): the 3-bit path uses them as one index into a table of
 //    centroid pairs (Section 5.3 "Merging Table Lookups", generalised to a 64-entry pair table
