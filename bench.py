@@ -172,7 +172,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=210)
-    ap.add_argument("--warmup", type=int, default=21)
+    ap.add_argument("--warmup", type=int, default=105)
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying HIP graphs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--detail", action="store_true", help="also print a per-(shape, b) table to stderr")
