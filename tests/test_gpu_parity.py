@@ -345,3 +345,22 @@ def test_quantised_model_end_to_end(B, batch):
         errs.append(float(np.sqrt(np.mean((y.astype(np.float64) - dense) ** 2))))
     assert errs[-1] < errs[0] / 8 and errs[3] < errs[0]
     pm.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_bit_widths_and_batches(B, seed):
+    # a seeded sweep over shapes the fixed cases do not name: any M, any K % 32 == 0 up to ~5 spans,
+    # random supported sets of bit-widths, every batch size; default dispatch
+    rng = np.random.default_rng([20240210, 99, seed])
+    for _ in range(8):
+        M = int(rng.integers(1, 300))
+        K = 32 * int(rng.integers(1, 330))
+        batch = int(rng.integers(1, 9))
+        bits = sorted(set(int(v) for v in rng.integers(3, 9, size=3)))
+        idx, luts, x = inputs.make_case(30 + seed, M, K, batch=batch, sigma=0.02, bit_widths=bits)
+        pm = B.ap_pack(idx, luts)
+        for b in bits:
+            y = run_gemv(pm, b, x)
+            check_against_oracle(y, idx, luts[b], b, x)
+        assert np.array_equal(B.ap_unpack(pm), idx)
+        pm.close()
