@@ -1,19 +1,35 @@
 """Build the HIP library in-tree: paper_2402_10517_amd/libapgemv.so (gfx950 only)."""
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libapgemv.so")
-SOURCES = ["gemv_kernels.hip", "api.cpp", "pack.cpp", "dense_gemm.cpp", "quantize.cpp"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+SOURCES = ["gemv_alu.hip", "gemv_matrix.hip", "dequant.hip", "dispatch.cpp", "api.cpp", "pack.cpp",
+           "dense_gemm.cpp", "quantize.cpp"]
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
 
 
 def build(verbose=False):
+    """Compile every source to an object file (in parallel, one hipcc per file), then link."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + ["-x", "hip"] + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB, "-ldl"]
+    os.makedirs(OBJ, exist_ok=True)
+
+    def compile_one(name):
+        obj = os.path.join(OBJ, name + ".o")
+        cmd = [hipcc] + FLAGS + ["-x", "hip", "-c", os.path.join(CSRC, name), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB, "-ldl"]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

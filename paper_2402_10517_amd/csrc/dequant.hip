@@ -1,0 +1,135 @@
+// Dequantise kernel (dense binary16 weights of the b-bit model) and the plain-read measurement kernel.
+#include "device_common.h"
+
+namespace apgemv {
+
+// Dequantise kernel (Section 6.2, "Matrix-Matrix Multiplication Performance": above a batch
+// threshold the engine dequantises the weights with a separate kernel and hands them to a dense
+// FP16 GEMM).  Same unit walk as the GEMV: a lane forms the table indices of its 32 slots of 4
+// rows and, instead of multiplying, writes the centroids as dense binary16: 8 consecutive columns
+// (16 bytes) per row and run, 1 KB contiguous per wave and row.
+template <int B>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 6))) void dequant_kernel(
+    const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
+    uint16_t *__restrict__ w, int M, int K)
+{
+    using T = Table<B>;
+    constexpr int TB = T::kRowBytes;
+    __shared__ __attribute__((aligned(16))) uint8_t tab[kRowsPerGroup * TB + 16];
+    __shared__ __attribute__((aligned(16))) uint16_t nat[kRowsPerGroup * 8];
+    const int g = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nwaves = blockDim.x >> 6;
+    const int row0 = g * kRowsPerGroup;
+    const int chunks = K / kChunkSlots;
+    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
+
+    StagedTable<B> st;
+    stage_tables_load<B>(st, lut, row0, M);
+    stage_tables_store<B>(st, tab, nat);
+    __syncthreads();
+    uint32_t one = 1;
+    asm("" : "+v"(one));
+    for (int span = wave; span < nspans; span += nwaves) {
+        const int rem = chunks - span * kSpanLanes;
+        const int nl = rem < kSpanLanes ? rem : kSpanLanes;
+        if (lane >= nl) continue;
+        const uint8_t *sbase = slices + ((size_t)g * chunks + (size_t)span * kSpanLanes) * 16;
+        u32x4 Q[B];
+#pragma unroll
+        for (int s = 0; s < B; ++s)
+            Q[s] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4 *>(sbase + (size_t)s * slice_bytes + (uint32_t)lane * 16u));
+#pragma unroll
+        for (int r = 0; r < kRowsPerGroup; ++r) {
+            const uint8_t *trow = tab + r * TB;
+            u32x4 out[4]; // out[t][j] = columns 2j, 2j+1 of run t
+            uint32_t W[8];
+            merge_row<B>(Q, r, W);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if constexpr (T::kPair) {
+                    const uint32_t v = W[2 * t];
+                    out[t][0] = *reinterpret_cast<const uint32_t *>(trow + byte_and<0>(v, 0xFCu));
+                    out[t][1] = *reinterpret_cast<const uint32_t *>(trow + byte_and<1>(v, 0xFCu));
+                    out[t][2] = *reinterpret_cast<const uint32_t *>(trow + byte_and<2>(v, 0xFCu));
+                    out[t][3] = *reinterpret_cast<const uint32_t *>(trow + byte_and<3>(v, 0xFCu));
+                } else {
+                    uint32_t a[2][4];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const uint32_t v = W[2 * t + h];
+                        a[h][0] = byte_to_addr<B, 0>(v, T::addr_mask(), one);
+                        a[h][1] = byte_to_addr<B, 1>(v, T::addr_mask(), one);
+                        a[h][2] = byte_to_addr<B, 2>(v, T::addr_mask(), one);
+                        a[h][3] = byte_to_addr<B, 3>(v, T::addr_mask(), one);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t w0 = *reinterpret_cast<const uint16_t *>(trow + a[0][j]);
+                        const uint32_t w1 = *reinterpret_cast<const uint16_t *>(trow + a[1][j]);
+                        out[t][j] = w0 | (w1 << 16);
+                    }
+                }
+            }
+            const int row = row0 + r;
+            if (row < M) {
+                uint16_t *wrow = w + (size_t)row * K + (size_t)span * kSpanCols + lane * 8;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    __builtin_nontemporal_store(out[t], reinterpret_cast<u32x4 *>(wrow + t * 8 * nl));
+            }
+        }
+    }
+}
+
+template <int B> static hipError_t launch_dequant_b(const GemvArgs &a, hipStream_t stream)
+{
+    const int groups = padded_rows(a.M) / kRowsPerGroup;
+    const int chunks = a.K / kChunkSlots;
+    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
+    const int nw = nspans < 8 ? nspans : 8;
+    hipLaunchKernelGGL((dequant_kernel<B>), dim3(groups), dim3(64 * nw), 0, stream, a.slices,
+                       a.slice_bytes, a.lut, a.y, a.M, a.K);
+    return hipGetLastError();
+}
+
+// a.y is the dense output (M*K binary16, row-major); a.x and a.batch are unused
+hipError_t launch_dequantize(const GemvArgs &a, hipStream_t stream)
+{
+    switch (a.b) {
+    case 3: return launch_dequant_b<3>(a, stream);
+    case 4: return launch_dequant_b<4>(a, stream);
+    case 5: return launch_dequant_b<5>(a, stream);
+    case 6: return launch_dequant_b<6>(a, stream);
+    case 7: return launch_dequant_b<7>(a, stream);
+    case 8: return launch_dequant_b<8>(a, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+// Plain read of known size with the slice loads' instruction and access shape (calibration of
+// profiling counters); each lane reads 4 x 16 bytes, a wave 4 x 1 KB.
+__global__ __launch_bounds__(256) void probe_read_kernel(const u32x4 *__restrict__ p, uint32_t *sink)
+{
+    const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    uint32_t a = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const u32x4 v = __builtin_nontemporal_load(p + (wave * 4 + k) * 64 + lane);
+        a ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+    }
+    if (a == 0x9e3779b9u && sink) *sink = a; // keeps the loads alive; sink is null in practice
+}
+
+hipError_t launch_probe_read(const void *dev_buf, size_t bytes, hipStream_t stream)
+{
+    const size_t blocks = bytes / 16384; // 256 threads x 64 bytes
+    hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       static_cast<const u32x4 *>(dev_buf), static_cast<uint32_t *>(nullptr));
+    return hipGetLastError();
+}
+
+} // namespace apgemv

@@ -1,0 +1,42 @@
+// Bit-width and kernel-family dispatch of one ap_gemv call: one stored matrix, the kernel and the
+// table are chosen per call (Section 5.2: only the first b slices and the b-bit table are touched).
+#include "launchers.h"
+#include "layout.h"
+
+namespace apgemv {
+
+hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream)
+{
+    if (a.b < 3 || a.b > 8) return hipErrorInvalidValue;
+    const int B = a.b;
+    // Which kernel for batch >= 2 was settled by measurement on the 70B shapes (8192x8192, 28672x8192,
+    // 8192x28672; all b):
+    //  * batch 2: the plain kernel (one group of rows per workgroup) wins everywhere;
+    //  * batch 5..8 with >= 2048 groups of rows: the matrix-core kernel with in-wave exchange, every b
+    //    (up to 24 % faster than the ALU kernels at b <= 5, level at b = 8);
+    //  * batch 3..4: that kernel for b >= 6 and, on the tallest matrices (>= 4096 groups), for b = 4, 5,
+    //    when every span has its own wave; b = 3 and short matrices stay on the plain kernel, long
+    //    rows at b >= 6 on the first matrix-core kernel.
+    // variant: 1 = never the in-wave-exchange kernel, 3 = whenever the shape allows (tuning overrides).
+    if (a.batch >= 2 && a.K % 128 == 0 && a.variant != 1) {
+        const int groups = padded_rows(a.M) / kRowsPerGroup;
+        const int nspans = (a.K / kChunkSlots + kSpanLanes - 1) / kSpanLanes;
+        const bool one_wave_per_span = nspans <= 8;
+        bool pays = false;
+        if (groups >= 2048 && a.row_groups_per_wg < 0 && a.mfma_min_batch == 0) {
+            if (a.batch >= 5) pays = true;
+            else if (a.batch >= 3 && one_wave_per_span) pays = B >= 6 || (B >= 4 && groups >= 4096);
+        }
+        if (a.variant == 3 || pays)
+            return launch_matrix_exchange(a, stream);
+    }
+    // The first matrix-core kernel (one row per lane): batch 3..8 at b >= 6 when the row length allows
+    // it; at b <= 5 the four rows' small tables of a block share LDS banks and it is slower
+    // (mfma_min_batch: tuning override; a negative value also lifts the b limit).
+    const int min_batch = a.mfma_min_batch > 0 ? a.mfma_min_batch : a.mfma_min_batch < 0 ? -a.mfma_min_batch : 3;
+    if (a.batch >= min_batch && a.K % 128 == 0 && (B >= 6 || a.mfma_min_batch < 0))
+        return launch_matrix_row_per_lane(a, stream);
+    return launch_alu(a, stream);
+}
+
+} // namespace apgemv

@@ -1,0 +1,338 @@
+// Any-precision GEMV kernels for gfx950 (CDNA4, wave64) and their launcher.
+//
+// Steps of one call (Any-Precision LLM, Section 5.2, the five thread-level operations): load the
+// first b bit slices of the lane's weights and the matching activations, turn the slices into
+// table indices, fetch centroids from the table rows staged in LDS, multiply-accumulate, reduce
+// over the lanes that share an output channel.  How each step is done differs from the paper's
+// kernel, which was written for 32-wide warps:
+//   * index formation needs no bit transpose: the slices are stored pre-rotated (layout.h), so the
+//     eight words of four table indices each come out of a shared three-level tree of bit-selects
+//     with constant masks (24 selects per 32 weights at 8 bits) and one rotate per word;
+//   * b = 3 looks two weights up at once in a 64-entry table of centroid pairs and feeds the
+//     pair to one packed dot product (Section 5.3 "Merging Table Lookups");
+//   * a lane keeps its 32 activations in registers for 4 output rows;
+//   * the reduction over lanes uses DPP row operations, then LDS across the waves of the group.
+#include "device_common.h"
+#include "launchers.h"
+
+namespace apgemv {
+
+// One workgroup per group of 4 rows; its waves stride over the row's spans of 2048 columns.
+// The table loads go out first, then the wave's first slice loads, then the tables are written to
+// LDS while the slice loads are still in flight; later
+// spans are loaded after the previous one is consumed (other waves of the CU cover the latency;
+// a second register set for prefetching cost more in occupancy than it gained).
+template <int B, int NB, int MAXT>
+__device__ __forceinline__ void gemv_group(const uint8_t *__restrict__ slices, size_t slice_bytes,
+                                           const uint16_t *__restrict__ lut, const uint16_t *__restrict__ x,
+                                           uint16_t *__restrict__ y, int M, int K, int batch, int g)
+{
+    using T = Table<B>;
+    constexpr int TB = T::kRowBytes;
+    __shared__ __attribute__((aligned(16))) uint8_t tab[kRowsPerGroup * TB + 16]; // + dummy area
+    __shared__ __attribute__((aligned(16))) uint16_t nat[kRowsPerGroup * 8];
+    __shared__ float red[MAXT / 64][NB][4][kRowsPerGroup]; // [wave][batch row][DPP row][lane & 3]
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform, kept in an SGPR
+    const int nwaves = blockDim.x >> 6;
+    const int row0 = g * kRowsPerGroup;
+    const int chunks = K / kChunkSlots;
+    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
+
+    u32x4 Q[B];
+    u32x4 X[NB][4];
+    // Loads of the lane's slice words and activations for one span (Section 5.2 step 1).
+    auto issue_loads = [&](int span) {
+        const int rem = chunks - span * kSpanLanes;
+        const int nl = rem < kSpanLanes ? rem : kSpanLanes;
+        {
+            // Lanes past the end of a ragged last span load what the last valid lane loads (and are
+            // masked out of the compute): no branch around the loads.
+            // wave-uniform base + 32-bit lane offset: the loads use the scalar-base address form
+            const uint8_t *sbase = slices + ((size_t)g * chunks + (size_t)span * kSpanLanes) * 16;
+            const uint32_t loff = (uint32_t)(lane < nl ? lane : nl - 1) * 16u;
+#pragma unroll
+            for (int s = 0; s < B; ++s)
+                Q[s] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4 *>(sbase + (size_t)s * slice_bytes + loff));
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int xr = nb < batch ? nb : batch - 1;
+                const uint8_t *xbase =
+                    reinterpret_cast<const uint8_t *>(x + (size_t)xr * K + (size_t)span * kSpanCols);
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    X[nb][t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)(t * 16 * nl) + loff);
+            }
+        }
+    };
+    auto active = [&](int span) { return lane < chunks - span * kSpanLanes; };
+
+    float acc[NB][kRowsPerGroup];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < kRowsPerGroup; ++r) acc[nb][r] = 0.f;
+
+    int span = wave; // the launcher guarantees nwaves <= nspans
+    StagedTable<B> st;
+    stage_tables_load<B>(st, lut, row0, M);
+    issue_loads(span);
+    stage_tables_store<B>(st, tab, nat); // waits for the table loads only
+    __syncthreads();
+    while (true) {
+        if (active(span)) compute_unit<B, NB>(Q, X, tab, acc);
+        span += nwaves;
+        if (span >= nspans) break;
+        issue_loads(span);
+    }
+
+    // ---- reduce over lanes, then over the waves of the group (fixed order: deterministic)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const float c = reduce4_in_dpp_rows(acc[nb], lane);
+        if ((lane & 15) >= 12) red[wave][nb][lane >> 4][lane & 3] = c;
+    }
+    __syncthreads();
+    if (threadIdx.x < kRowsPerGroup * NB) {
+        const int nb = threadIdx.x / kRowsPerGroup, r = threadIdx.x % kRowsPerGroup;
+        const int cls = ((r & 1) << 1) | (r >> 1); // lane & 3 that holds row r
+        float s = 0.f;
+        for (int w = 0; w < nwaves; ++w)
+            for (int d = 0; d < 4; ++d) s += red[w][nb][d][cls];
+        const int row = row0 + r;
+        if (row < M && nb < batch) {
+            const __half h = __float2half_rn(s);
+            y[(size_t)nb * M + row] = __builtin_bit_cast(uint16_t, h);
+        }
+    }
+}
+
+template <int B, int NB, int MAXT>
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, (B <= 4 && NB == 1) ? 8 : 6))) void gemv_kernel(
+    const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
+    const uint16_t *__restrict__ x, uint16_t *__restrict__ y, int M, int K, int batch)
+{
+    gemv_group<B, NB, MAXT>(slices, slice_bytes, lut, x, y, M, K, batch, blockIdx.x);
+}
+
+// Several matrices with the same row length in one launch (the q/k/v or gate/up projections of
+// a decoder layer): workgroup -> (matrix, group of 4 rows) through the prefix sums of the group
+// counts.  Each matrix keeps its own activations and outputs; the work per group is that of
+// gemv_kernel, so results are bit-identical to separate calls that use it.
+template <int B, int NB, int MAXT>
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 6))) void gemv_multi_kernel(MultiArgs a)
+{
+    int m = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxMulti; ++i)
+        if (i < a.count && (int)blockIdx.x >= a.group_begin[i]) m = i;
+    gemv_group<B, NB, MAXT>(a.slices[m], a.slice_bytes[m], a.lut[m], a.x[m], a.y[m], a.M[m], a.K, a.batch,
+                            (int)blockIdx.x - a.group_begin[m]);
+}
+
+// Variant for matrices with many rows and for batches: one workgroup owns up to kMaxRowGroups
+// consecutive groups of 4 rows and each wave keeps its activations (one span, all batch rows) in
+// registers across them, so activation traffic through the caches drops by that factor and the
+// per-wave set-up is paid once.  The slice words of the next group are loaded while the current
+// group is processed.  Requires one wave per span (the launcher checks).
+constexpr int kMaxRowGroups = 4;
+
+template <int B, int NB, int MAXT>
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(1, 6))) void gemv_rows_kernel(
+    const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
+    const uint16_t *__restrict__ x, uint16_t *__restrict__ y, int M, int K, int batch, int rg_per_wg)
+{
+    using T = Table<B>;
+    constexpr int TB = T::kRowBytes;
+    constexpr int kGroupBytes = kRowsPerGroup * TB;
+    __shared__ __attribute__((aligned(16))) uint8_t tab[kMaxRowGroups * kGroupBytes];
+    __shared__ __attribute__((aligned(16))) uint16_t nat[kMaxRowGroups * kRowsPerGroup * 8];
+    __shared__ float red[MAXT / 64][kMaxRowGroups][NB][4][kRowsPerGroup];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform, kept in an SGPR
+    const int nwaves = blockDim.x >> 6;
+    const int tid = threadIdx.x, nth = blockDim.x;
+    const int groups = (M + kRowsPerGroup - 1) / kRowsPerGroup;
+    const int g0 = blockIdx.x * rg_per_wg;
+    const int ng = groups - g0 < rg_per_wg ? groups - g0 : rg_per_wg;
+    const int row0 = g0 * kRowsPerGroup;
+    const int nrows = M - row0 < ng * kRowsPerGroup ? M - row0 : ng * kRowsPerGroup; // valid rows here
+    const int chunks = K / kChunkSlots;
+    const int span = wave; // one wave per span
+    const int rem = chunks - span * kSpanLanes;
+    const int nl = rem < kSpanLanes ? rem : kSpanLanes;
+    const bool active = lane < nl;
+    const uint32_t loff = (uint32_t)(active ? lane : nl - 1) * 16u;
+
+    auto load_q = [&](u32x4 (&Q)[B], int rg) {
+        const uint8_t *sbase = slices + ((size_t)(g0 + rg) * chunks + (size_t)span * kSpanLanes) * 16;
+#pragma unroll
+        for (int s = 0; s < B; ++s)
+            Q[s] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4 *>(sbase + (size_t)s * slice_bytes + loff));
+    };
+
+    u32x4 X[NB][4];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int xr = nb < batch ? nb : batch - 1;
+        const uint8_t *xbase = reinterpret_cast<const uint8_t *>(x + (size_t)xr * K + (size_t)span * kSpanCols);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            X[nb][t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)(t * 16 * nl) + loff);
+    }
+    u32x4 QA[B], QB[B];
+    load_q(QA, 0);
+
+    // ---- tables of all the groups of this workgroup (rows are contiguous in the stored tables)
+    if constexpr (B == 3) {
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(lut + (size_t)row0 * 8);
+        for (int i = tid; i < ng * kRowsPerGroup * 4; i += nth)
+            reinterpret_cast<uint32_t *>(nat)[i] = (i >> 2) < nrows ? src[i] : 0u;
+        __syncthreads();
+        for (int i = tid; i < ng * kRowsPerGroup * 64; i += nth) {
+            const int r = i >> 6, i6 = i & 63;
+            const int a = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
+            const int c = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
+            const uint32_t v = (uint32_t)nat[r * 8 + a] | ((uint32_t)nat[r * 8 + c] << 16);
+            *reinterpret_cast<uint32_t *>(tab + r * TB + i6 * 4) = v;
+        }
+    } else if constexpr (B >= 6) {
+        constexpr int kPerRow = TB / 16;
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(lut + ((size_t)row0 << B));
+        for (int i = tid; i < ng * kRowsPerGroup * kPerRow; i += nth)
+            reinterpret_cast<u32x4 *>(tab)[i] = i / kPerRow < nrows ? src[i] : u32x4{0, 0, 0, 0};
+    } else {
+        constexpr int kDwordsPerRow = (1 << B) / 2;
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(lut + ((size_t)row0 << B));
+        for (int i = tid; i < ng * kRowsPerGroup * kDwordsPerRow; i += nth) {
+            const int r = i / kDwordsPerRow, k = i % kDwordsPerRow;
+            const uint32_t v = r < nrows ? src[i] : 0u;
+            uint8_t *dst = tab + r * TB + T::stored_addr(2 * k);
+            *reinterpret_cast<uint16_t *>(dst) = (uint16_t)v;
+            *reinterpret_cast<uint16_t *>(dst + 4) = (uint16_t)(v >> 16);
+        }
+    }
+    __syncthreads();
+
+    auto process = [&](const u32x4 (&Q)[B], int rg) {
+        float acc[NB][kRowsPerGroup];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < kRowsPerGroup; ++r) acc[nb][r] = 0.f;
+        if (active) compute_unit<B, NB>(Q, X, tab + rg * kGroupBytes, acc);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const float c = reduce4_in_dpp_rows(acc[nb], lane);
+            if ((lane & 15) >= 12) red[wave][rg][nb][lane >> 4][lane & 3] = c;
+        }
+    };
+    for (int rg = 0; rg < ng; rg += 2) {
+        if (rg + 1 < ng) load_q(QB, rg + 1);
+        process(QA, rg);
+        if (rg + 1 >= ng) break;
+        if (rg + 2 < ng) load_q(QA, rg + 2);
+        process(QB, rg + 1);
+    }
+    __syncthreads();
+    for (int i = tid; i < ng * kRowsPerGroup * NB; i += nth) {
+        const int rg = i / (kRowsPerGroup * NB), nb = (i / kRowsPerGroup) % NB, r = i % kRowsPerGroup;
+        const int cls = ((r & 1) << 1) | (r >> 1); // lane & 3 that holds row r
+        float s = 0.f;
+        for (int w = 0; w < nwaves; ++w)
+            for (int d = 0; d < 4; ++d) s += red[w][rg][nb][d][cls];
+        const int row = row0 + rg * kRowsPerGroup + r;
+        if (row < M && nb < batch) {
+            const __half h = __float2half_rn(s);
+            y[(size_t)nb * M + row] = __builtin_bit_cast(uint16_t, h);
+        }
+    }
+}
+
+template <int B, int NB>
+static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
+{
+    // Up to 8 waves per group at batch 1 and 2 (measured best across the Llama shapes: long rows
+    // then take two spans per wave); batch 4 and 8 hold 4 or 8 activation rows in registers and
+    // are capped at 4 waves.
+    constexpr int kMaxWaves = NB <= 4 ? 8 : 4;
+    constexpr int kMaxThreads = 64 * kMaxWaves;
+    const int groups = padded_rows(a.M) / kRowsPerGroup;
+    const int chunks = a.K / kChunkSlots;
+    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
+    int nw = kMaxWaves;
+    if (a.waves_per_group > 0 && a.waves_per_group < nw) nw = a.waves_per_group;
+    if (nw > nspans) nw = nspans;
+    // several row groups per workgroup at batch 5..8 when every span has its own wave and there are
+    // enough groups to keep the device full (at batch 2..4 the plain kernel measured faster)
+    int rg = a.row_groups_per_wg;
+    if (rg < 0) rg = (nspans <= kMaxWaves && groups >= 2048 && NB >= 8) ? kMaxRowGroups : 1;
+    if (rg > kMaxRowGroups) rg = kMaxRowGroups;
+    if (rg > 1 && nspans <= kMaxWaves) {
+        hipLaunchKernelGGL((gemv_rows_kernel<B, NB, kMaxThreads>), dim3((groups + rg - 1) / rg),
+                           dim3(64 * nspans), 0, stream, a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M,
+                           a.K, a.batch, rg);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL((gemv_kernel<B, NB, kMaxThreads>), dim3(groups), dim3(64 * nw), 0, stream,
+                       a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
+    return hipGetLastError();
+}
+
+// The ALU kernels for one call: template instance by bit-width and by batch rounded up to 1, 2, 4, 8.
+template <int B> static hipError_t launch_alu_b(const GemvArgs &a, hipStream_t stream)
+{
+    if (a.batch == 1) return launch_one<B, 1>(a, stream);
+    if (a.batch == 2) return launch_one<B, 2>(a, stream);
+    if (a.batch <= 4) return launch_one<B, 4>(a, stream);
+    return launch_one<B, 8>(a, stream);
+}
+hipError_t launch_alu(const GemvArgs &a, hipStream_t stream)
+{
+    switch (a.b) {
+    case 3: return launch_alu_b<3>(a, stream);
+    case 4: return launch_alu_b<4>(a, stream);
+    case 5: return launch_alu_b<5>(a, stream);
+    case 6: return launch_alu_b<6>(a, stream);
+    case 7: return launch_alu_b<7>(a, stream);
+    case 8: return launch_alu_b<8>(a, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <int B, int NB> static hipError_t launch_multi_one(const MultiArgs &a, int total_groups, hipStream_t stream)
+{
+    constexpr int kMaxWaves = NB <= 4 ? 8 : 4;
+    const int chunks = a.K / kChunkSlots;
+    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
+    const int nw = nspans < kMaxWaves ? nspans : kMaxWaves;
+    hipLaunchKernelGGL((gemv_multi_kernel<B, NB, 64 * kMaxWaves>), dim3(total_groups), dim3(64 * nw), 0, stream, a);
+    return hipGetLastError();
+}
+
+template <int B> static hipError_t launch_multi_b(const MultiArgs &a, int total_groups, hipStream_t stream)
+{
+    if (a.batch == 1) return launch_multi_one<B, 1>(a, total_groups, stream);
+    if (a.batch == 2) return launch_multi_one<B, 2>(a, total_groups, stream);
+    if (a.batch <= 4) return launch_multi_one<B, 4>(a, total_groups, stream);
+    return launch_multi_one<B, 8>(a, total_groups, stream);
+}
+
+hipError_t launch_gemv_multi(const MultiArgs &a, int b, int total_groups, hipStream_t stream)
+{
+    switch (b) {
+    case 3: return launch_multi_b<3>(a, total_groups, stream);
+    case 4: return launch_multi_b<4>(a, total_groups, stream);
+    case 5: return launch_multi_b<5>(a, total_groups, stream);
+    case 6: return launch_multi_b<6>(a, total_groups, stream);
+    case 7: return launch_multi_b<7>(a, total_groups, stream);
+    case 8: return launch_multi_b<8>(a, total_groups, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+} // namespace apgemv
