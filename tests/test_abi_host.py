@@ -180,3 +180,19 @@ def test_error_paths_before_any_device_work():
 
 def test_algorithmic_bytes_formula():
     assert inputs.algorithmic_bytes(4096, 4096, 3) == 4096 * 4096 * 3 // 8 + 4096 * 16 + 8192 + 8192
+
+
+def test_binding_fails_loudly_without_the_library(tmp_path):
+    # a copy of the package without libapgemv.so must refuse to import (no CPU fallback exists)
+    import shutil
+    import subprocess
+    import sys
+    pkg = os.path.join(os.path.dirname(os.path.abspath(__file__)), "..", "paper_2402_10517_amd")
+    dst = tmp_path / "paper_2402_10517_amd"
+    dst.mkdir()
+    for name in ("__init__.py", "binding.py", "inputs.py", "build.py"):
+        shutil.copy(os.path.join(pkg, name), dst / name)
+    r = subprocess.run([sys.executable, "-c", "import paper_2402_10517_amd.binding"], cwd=tmp_path,
+                       capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "ImportError" in r.stderr and "libapgemv.so is not built" in r.stderr
