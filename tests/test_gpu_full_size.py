@@ -40,12 +40,12 @@ def test_config3_llama13b_shapes_sampled_rows(B, M, K):
 
 @pytest.mark.parametrize("M,K", inputs.CONFIGS[5]["shapes"])
 def test_config5_llama70b_shapes_small_batch_sampled_rows(B, M, K):
-    idx, luts, x = inputs.make_case(5, M, K, batch=8, sigma=0.01, bit_widths=[3, 5, 8])
+    idx, luts, x = inputs.make_case(5, M, K, batch=8, sigma=0.01)
     pm = B.ap_pack(idx, luts)
     rows = np.unique(np.concatenate([np.arange(0, 4), np.arange(M - 4, M),
                                      np.random.default_rng(K).integers(0, M, size=256)]))
-    for b in (3, 5, 8):
-        for batch in (1, 2, 4, 8):
+    for b in ALL_BITS:
+        for batch in (1, 2, 3, 4, 8):
             y = run_gemv(pm, b, x[:batch])
             check_against_oracle(y, idx, luts[b], b, x[:batch], rows=rows)
     pm.close()
