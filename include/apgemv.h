@@ -112,6 +112,37 @@ ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int
                   void *stream);
 
 /*
+ * Kernel-selection overrides of one handle, for tests (to reach every kernel variant on small shapes)
+ * and for A/B measurements; production callers set none.  ap_gemv chooses the kernel from (b, batch,
+ * shape); an override replaces part of that choice.  Every variant meets the same tolerance, but the
+ * bit-identity statements below (repeated calls, ap_gemv_multi) assume that the options of a handle
+ * do not change between the calls compared.  Not thread-safe against concurrent calls on the handle.
+ *   AP_OPT_WAVES_PER_GROUP    1..8 waves per group of 4 rows in the batch-1 kernels; 0 = from the shape
+ *   AP_OPT_ROW_GROUPS_PER_WG  1..4 groups of 4 rows per workgroup (forces the row-group kernels);
+ *                             -1 = from the shape
+ *   AP_OPT_MFMA_MIN_BATCH     smallest batch sent to the one-row-per-lane matrix-core kernel (1..9,
+ *                             9 = never); a negative value -m means m and also lifts its b >= 6 limit;
+ *                             0 = default (3)
+ *   AP_OPT_VARIANT            AP_VARIANT_AUTO; AP_VARIANT_NO_EXCHANGE = never the matrix-core kernel
+ *                             with in-wave exchange; AP_VARIANT_EXCHANGE = that kernel whenever the
+ *                             shape allows (batch >= 2, K % 128 == 0); AP_VARIANT_BANK_PER_LANE = at
+ *                             batch 1, b >= 7: the kernel in which every lane looks up its own LDS
+ *                             bank column (8 copies of each row's table) instead of the default
+ * AP_ERR_INVALID_ARG for an unknown option or a value outside its range.
+ */
+typedef enum {
+    AP_OPT_WAVES_PER_GROUP = 0,
+    AP_OPT_ROW_GROUPS_PER_WG = 1,
+    AP_OPT_MFMA_MIN_BATCH = 2,
+    AP_OPT_VARIANT = 3
+} ap_option;
+#define AP_VARIANT_AUTO 0
+#define AP_VARIANT_NO_EXCHANGE 1
+#define AP_VARIANT_EXCHANGE 3
+#define AP_VARIANT_BANK_PER_LANE 5
+ap_status ap_set_option(ap_matrix *h, int option, int value);
+
+/*
  * Several GEMVs of the same bit-width in ONE launch: y_i = W_i,b * x_i for i < count (1..8), e.g. the
  * q/k/v or the gate/up projections of a decoder layer (Section 6.3 measures whole-model decoding,
  * where the per-launch cost of 224 small GEMVs per token matters).  All matrices must have the same

@@ -22,9 +22,13 @@ STATUS_NAMES = {0: "AP_OK", 1: "AP_ERR_INVALID_ARG", 2: "AP_ERR_SHAPE", 3: "AP_E
                 7: "AP_ERR_HIP"}
 
 EXPORTS = ["ap_packed_size", "ap_pack_host", "ap_unpack_host", "ap_blob_lut_entry",
-           "ap_read_extent", "ap_pack", "ap_attach", "ap_unpack", "ap_gemv", "ap_gemv_multi", "ap_dequantize",
+           "ap_read_extent", "ap_pack", "ap_attach", "ap_set_option", "ap_unpack", "ap_gemv", "ap_gemv_multi", "ap_dequantize",
            "ap_gemm_workspace_size", "ap_gemm", "ap_quantize", "ap_probe_read", "ap_matrix_info",
            "ap_free", "ap_strerror"]
+
+
+OPTIONS = {"waves": 0, "row_groups": 1, "mfma_min_batch": 2, "variant": 3}
+VARIANT_AUTO, VARIANT_NO_EXCHANGE, VARIANT_EXCHANGE, VARIANT_BANK_PER_LANE = 0, 1, 3, 5
 
 
 class ApError(RuntimeError):
@@ -47,6 +51,7 @@ def _load():
     L.ap_read_extent.argtypes = [ci, ci, ci, cu, ci, psz, psz, psz, psz]
     L.ap_pack.argtypes = [vp, ci, ci, ci, vp, vp, sz, vp, ctypes.POINTER(vp)]
     L.ap_attach.argtypes = [vp, sz, vp, ctypes.POINTER(vp)]
+    L.ap_set_option.argtypes = [vp, ci, ci]
     L.ap_unpack.argtypes = [vp, vp, vp]
     L.ap_gemv.argtypes = [vp, ci, vp, vp, ci, vp]
     L.ap_gemv_multi.argtypes = [vp, ci, ci, ci, vp]
@@ -153,6 +158,12 @@ class PackedMatrix:
             self.close()
         except Exception:
             pass
+
+    def set_options(self, **opts):
+        """Kernel-selection overrides (tests, A/B runs): waves, row_groups, mfma_min_batch, variant."""
+        for name, value in opts.items():
+            _check(lib.ap_set_option(self.handle, OPTIONS[name], int(value)), "ap_set_option(%s)" % name)
+        return self
 
     def clone(self):
         """Device-to-device copy of the blob, adopted through ap_attach (distinct addresses)."""

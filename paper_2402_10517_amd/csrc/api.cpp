@@ -1,50 +1,23 @@
 // C-ABI entry points that touch the device: upload, download, attach, GEMV dispatch.
 #include <hip/hip_runtime_api.h>
 
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
 
 #include "dense_gemm.h"
+#include "handle.h"
 #include "kernels.h"
 #include "pack.h"
 
 using namespace apgemv;
 
-struct ap_matrix {
-    uint32_t tag;
-    BlobHeader hdr;
-    uint8_t *dev;
-    int waves_per_group;
-    int row_groups_per_wg;
-    int mfma_min_batch;
-    int variant;
-};
-static constexpr uint32_t kHandleTag = 0x41504d58u;
-
-static bool handle_ok(const ap_matrix *h) { return h && h->tag == kHandleTag && h->dev; }
-
-// Tuning overrides for experiments: waves per row group, row groups per workgroup.
-static int env_waves()
+static void default_tuning(ap_matrix *h)
 {
-    const char *e = std::getenv("APGEMV_WAVES");
-    return e ? std::atoi(e) : 0;
-}
-static int env_mfma_min_batch()
-{
-    const char *e = std::getenv("APGEMV_MFMA_MIN_BATCH");
-    return e ? std::atoi(e) : 0;
-}
-static int env_variant()
-{
-    const char *e = std::getenv("APGEMV_VARIANT");
-    return e ? std::atoi(e) : 0;
-}
-static int env_row_groups()
-{
-    const char *e = std::getenv("APGEMV_ROW_GROUPS");
-    return e ? std::atoi(e) : -1;
+    h->waves_per_group = 0;
+    h->row_groups_per_wg = -1;
+    h->mfma_min_batch = 0;
+    h->variant = 0;
 }
 
 extern "C" ap_status ap_pack(const uint8_t *idx_host, int M, int K, int n,
@@ -82,10 +55,7 @@ extern "C" ap_status ap_pack(const uint8_t *idx_host, int M, int K, int n,
     h->tag = kHandleTag;
     h->hdr = hdr;
     h->dev = static_cast<uint8_t *>(dev_buf);
-    h->waves_per_group = env_waves();
-    h->row_groups_per_wg = env_row_groups();
-    h->mfma_min_batch = env_mfma_min_batch();
-    h->variant = env_variant();
+    default_tuning(h);
     *out = h;
     return AP_OK;
 }
@@ -106,12 +76,35 @@ extern "C" ap_status ap_attach(void *dev_buf, size_t dev_buf_bytes, void *stream
     h->tag = kHandleTag;
     h->hdr = hdr;
     h->dev = static_cast<uint8_t *>(dev_buf);
-    h->waves_per_group = env_waves();
-    h->row_groups_per_wg = env_row_groups();
-    h->mfma_min_batch = env_mfma_min_batch();
-    h->variant = env_variant();
+    default_tuning(h);
     *out = h;
     return AP_OK;
+}
+
+extern "C" ap_status ap_set_option(ap_matrix *h, int option, int value)
+{
+    if (!handle_ok(h)) return AP_ERR_INVALID_ARG;
+    switch (option) {
+    case AP_OPT_WAVES_PER_GROUP:
+        if (value < 0 || value > 8) return AP_ERR_INVALID_ARG;
+        h->waves_per_group = value;
+        return AP_OK;
+    case AP_OPT_ROW_GROUPS_PER_WG:
+        if (value < -1 || value == 0 || value > 4) return AP_ERR_INVALID_ARG;
+        h->row_groups_per_wg = value;
+        return AP_OK;
+    case AP_OPT_MFMA_MIN_BATCH:
+        if (value < -9 || value > 9) return AP_ERR_INVALID_ARG;
+        h->mfma_min_batch = value;
+        return AP_OK;
+    case AP_OPT_VARIANT:
+        if (value != AP_VARIANT_AUTO && value != AP_VARIANT_NO_EXCHANGE && value != AP_VARIANT_EXCHANGE &&
+            value != AP_VARIANT_BANK_PER_LANE)
+            return AP_ERR_INVALID_ARG;
+        h->variant = value;
+        return AP_OK;
+    }
+    return AP_ERR_INVALID_ARG;
 }
 
 extern "C" ap_status ap_unpack(const ap_matrix *h, uint8_t *idx_host_out, void *stream)

@@ -9,6 +9,10 @@ hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream)
 {
     if (a.b < 3 || a.b > 8) return hipErrorInvalidValue;
     const int B = a.b;
+    // Bank-per-lane lookups at batch 1, b = 7, 8: conflict-free, but two operations per table address
+    // and 8 copies of every table; measured slower than the shared-table kernel on every Llama shape
+    // (b = 8: 8.2 / 17.7 / 19.6 us against 6.8 / 12.0 / 12.7 us on the 7B shapes), so only on request.
+    if (a.batch == 1 && B >= 7 && a.variant == 5) return launch_quad(a, stream);
     // Which kernel for batch >= 2 was settled by measurement on the 70B shapes (8192x8192, 28672x8192,
     // 8192x28672; all b):
     //  * batch 2: the plain kernel (one group of rows per workgroup) wins everywhere;

@@ -18,8 +18,9 @@ struct GemvArgs {
     int waves_per_group;   // 0 = choose from the shape
     int row_groups_per_wg; // -1 = choose from the shape; 1 = one group of 4 rows per workgroup
     int mfma_min_batch;    // 0 = default (3); batches below it use the ALU kernels; 9 = never
-    int variant;           // 0 = choose; 1 = never the matrix-core kernel with in-wave exchange; 3 = whenever
-                           // the shape allows it (batch >= 2, K % 128 == 0)
+    int variant;           // AP_VARIANT_*: 0 = choose; 1 = never the matrix-core kernel with in-wave exchange;
+                           // 3 = that kernel whenever the shape allows it (batch >= 2, K % 128 == 0);
+                           // 5 = the bank-per-lane kernel at batch 1, b >= 7
 };
 
 constexpr int kMaxMulti = 8;

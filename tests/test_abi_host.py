@@ -175,6 +175,7 @@ def test_error_paths_before_any_device_work():
     assert L.ap_gemv(None, 4, fake_dev, fake_dev, 1, None) == 1
     assert L.ap_unpack(None, idx.ctypes.data, None) == 1
     assert L.ap_matrix_info(None, None, None, None, None) == 1
+    assert L.ap_set_option(None, 0, 1) == 1
     L.ap_free(None)
 
 

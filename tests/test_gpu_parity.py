@@ -149,13 +149,12 @@ def test_subnormal_centroids_are_not_flushed(B, b, batch):
 
 @pytest.mark.parametrize("rg", [2, 3, 4])
 @pytest.mark.parametrize("batch", [1, 2, 5, 8])
-def test_several_row_groups_per_workgroup(B, monkeypatch, rg, batch):
+def test_several_row_groups_per_workgroup(B, rg, batch):
     # the variant that keeps activations in registers across row groups, forced on small ragged
     # shapes: rows not a multiple of 4*rg, a ragged last span, 1..4 waves per group
-    monkeypatch.setenv("APGEMV_ROW_GROUPS", str(rg))
     for (M, K) in [(4 * rg * 3 + 5, 2048 + 160), (7, 96), (4 * rg + 1, 3 * 2048 + 32 * 17)]:
         idx, luts, x = inputs.make_case(18, M, K, batch=batch, sigma=0.01)
-        pm = B.ap_pack(idx, luts)
+        pm = B.ap_pack(idx, luts).set_options(row_groups=rg)
         for b in ALL_BITS:
             y = run_gemv(pm, b, x)
             check_against_oracle(y, idx, luts[b], b, x)
@@ -163,15 +162,13 @@ def test_several_row_groups_per_workgroup(B, monkeypatch, rg, batch):
 
 
 @pytest.mark.parametrize("batch", [3, 4, 5, 8])
-def test_matrix_core_variant_for_every_bit_width(B, monkeypatch, batch):
+def test_matrix_core_variant_for_every_bit_width(B, batch):
     # forced for every b (the dispatcher uses it for b >= 6 only): several spans, a ragged last span
     # of 4-chunk blocks, rows not a multiple of 4 or 16, one and four row groups per workgroup
-    monkeypatch.setenv("APGEMV_MFMA_MIN_BATCH", "-3")
-    for rg in ("1", "4"):
-        monkeypatch.setenv("APGEMV_ROW_GROUPS", rg)
+    for rg in (1, 4):
         for (M, K) in [(37, 128), (70, 2048 + 640), (21, 3 * 2048 + 128)]:
             idx, luts, x = inputs.make_case(19, M, K, batch=batch, sigma=0.01)
-            pm = B.ap_pack(idx, luts)
+            pm = B.ap_pack(idx, luts).set_options(mfma_min_batch=-3, row_groups=rg)
             for b in ALL_BITS:
                 y = run_gemv(pm, b, x)
                 check_against_oracle(y, idx, luts[b], b, x)
@@ -179,20 +176,33 @@ def test_matrix_core_variant_for_every_bit_width(B, monkeypatch, batch):
 
 
 @pytest.mark.parametrize("batch", [2, 3, 4, 5, 7, 8])
-def test_matrix_core_variant_with_in_block_exchange(B, monkeypatch, batch):
+def test_matrix_core_variant_with_in_block_exchange(B, batch):
     # forced for every b and batch >= 2: one span, several spans with a ragged last span of 4-chunk
     # blocks, more spans than waves (a wave takes two spans), rows not a multiple of 4
     # one, two and four row groups per workgroup (the last two reuse the activations of a span)
-    monkeypatch.setenv("APGEMV_VARIANT", "3")
-    for rg in ("1", "2", "4"):
-        monkeypatch.setenv("APGEMV_ROW_GROUPS", rg)
+    for rg in (1, 2, 4):
         for (M, K) in [(37, 128), (70, 2048 + 640), (21, 3 * 2048 + 128), (9, 9 * 2048 + 256)]:
             idx, luts, x = inputs.make_case(21, M, K, batch=batch, sigma=0.01)
-            pm = B.ap_pack(idx, luts)
+            pm = B.ap_pack(idx, luts).set_options(variant=B.VARIANT_EXCHANGE, row_groups=rg)
             for b in ALL_BITS:
                 y = run_gemv(pm, b, x)
                 check_against_oracle(y, idx, luts[b], b, x)
             pm.close()
+
+
+@pytest.mark.parametrize("b", [7, 8])
+def test_bank_per_lane_variant(B, b):
+    # forced (the dispatcher does not choose it): one lane per LDS bank column, 8 copies of a table,
+    # a lane owns one row of 4 chunks: ragged spans whose last quad is partly filled, rows not a
+    # multiple of 4, 1..8 waves per group (1, 2, 4, 8 or 16 table pieces per thread), unsorted tables
+    rng = np.random.default_rng(40 + b)
+    for (M, K) in RAGGED + [(512, 512), (33, 8 * 2048), (6, 14 * 2048)]:
+        idx, luts, x = inputs.make_case(24, M, K, bit_widths=[b])
+        lut = luts[b][:, rng.permutation(1 << b)].copy()
+        pm = B.ap_pack(idx, {b: lut}).set_options(variant=B.VARIANT_BANK_PER_LANE)
+        y = run_gemv(pm, b, x)
+        check_against_oracle(y, idx, lut, b, x)
+        pm.close()
 
 
 @pytest.mark.parametrize("batch", [1, 2, 8])
@@ -302,6 +312,16 @@ def test_output_canaries_and_sparse_support(B):
     assert B.lib.ap_gemv(pm.handle, 3, xd.data_ptr(), ybuf.data_ptr(), 9, sp) == 6
     assert B.lib.ap_gemv(pm.handle, 3, xd.data_ptr() + 2, ybuf.data_ptr(), 1, sp) == 1
     pm.close()
+
+
+def test_option_values_are_checked(B, tiny):
+    _, _, _, pm = tiny
+    L = B.lib
+    for opt, bad in ((0, 9), (0, -1), (1, 0), (1, 5), (2, 10), (3, 2), (3, 7), (9, 0)):
+        assert L.ap_set_option(pm.handle, opt, bad) == 1, (opt, bad)
+    for opt, good, default in ((0, 2, 0), (1, 1, -1), (2, 9, 0), (3, 1, 0)):
+        assert L.ap_set_option(pm.handle, opt, good) == 0
+        assert L.ap_set_option(pm.handle, opt, default) == 0
 
 
 def test_smaller_parent_bit_width(B):
