@@ -182,6 +182,24 @@ ap_status ap_gemm(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int
                   void *work_dev, size_t work_bytes, void *stream);
 
 /*
+ * ap_gemm for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same result contract as ap_gemm (binary32 accumulation,
+ * binary16 output, the tolerance of ap_gemv), but the call allocates nothing and calls no library that
+ * might: the dequantised weights go to a device array built into this library, AP_GEMM_STATIC_MAX_BYTES
+ * large (each GPU the library runs on holds its own copy until the process ends), and the product is
+ * computed by a kernel of this library.  The array's device address is looked up once per device, by
+ * ap_pack / ap_attach or else by the first call here.
+ *   x_dev   device, batch*K binary16 row-major, 16-byte aligned;  y_dev  device, batch*M binary16
+ *   AP_ERR_BUFFER_TOO_SMALL if M*K*2 > AP_GEMM_STATIC_MAX_BYTES (use ap_gemm with your own workspace)
+ * All calls on one GPU share the one array: calls that may overlap in time on the same GPU (different
+ * streams, or threads) race on it and must be serialised by the caller.  The array keeps the last
+ * call's weights; every call rewrites all it reads, so nothing needs clearing.
+ */
+#define AP_GEMM_STATIC_MAX_BYTES (32u << 20)
+ap_status ap_gemm_static(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int batch,
+                         void *stream);
+
+/*
  * Host-only any-precision quantiser (no HIP call): incremental upscaling of Section 4.  Every output
  * channel (row of w) is clustered on its own: a seed model of n_seed bits from a weighted 1-D k-means
  * (weights = sens, the per-weight sensitivities; NULL = all ones), then for b = n_seed..n-1 every

@@ -56,6 +56,7 @@ extern "C" ap_status ap_pack(const uint8_t *idx_host, int M, int K, int n,
     h->hdr = hdr;
     h->dev = static_cast<uint8_t *>(dev_buf);
     default_tuning(h);
+    static_scratch_setup(); // set-up time: ap_gemm_static then finds its array without a lookup
     *out = h;
     return AP_OK;
 }
@@ -77,6 +78,7 @@ extern "C" ap_status ap_attach(void *dev_buf, size_t dev_buf_bytes, void *stream
     h->hdr = hdr;
     h->dev = static_cast<uint8_t *>(dev_buf);
     default_tuning(h);
+    static_scratch_setup(); // set-up time: ap_gemm_static then finds its array without a lookup
     *out = h;
     return AP_OK;
 }

@@ -39,6 +39,9 @@ hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream);
 hipError_t launch_gemv_multi(const MultiArgs &a, int b, int total_groups, hipStream_t stream);
 hipError_t launch_dequantize(const GemvArgs &a, hipStream_t stream);
 hipError_t launch_probe_read(const void *dev_buf, size_t bytes, hipStream_t stream);
+// Looks up, once per device, the device address of the static array ap_gemm_static writes the dense
+// weights to (the current device's copy); called where a matrix is set up on a device.
+bool static_scratch_setup();
 
 } // namespace apgemv
 #endif
