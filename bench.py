@@ -128,9 +128,25 @@ def decode_step(args, np, torch, B, inputs, dev):
             if B.lib.ap_gemv_multi(arr, len(arr), b, 1, sp) != 0:
                 raise RuntimeError("ap_gemv_multi failed")
 
+    # work lists (ap_gemv_list): a whole layer per launch (7 items), and 32 items per launch (the 224
+    # matrices of config 4 are independent of each other: 7 launches per step)
+    layer_lists, wide_lists = {}, {}
+    for b in range(3, 9):
+        quads = [(lay[i][2], b, lay[i][3], ys[i]) for lay, ys in zip(model, youts) for i in range(len(lay))]
+        layer_lists[b] = [B.make_list(quads[k:k + 7]) for k in range(0, len(quads), 7)]
+        wide_lists[b] = [B.make_list(quads[k:k + 32]) for k in range(0, len(quads), 32)]
+
+    def issue_lists(lists):
+        def fn(b):
+            for arr in lists[b]:
+                if B.lib.ap_gemv_list(arr, len(arr), sp) != 0:
+                    raise RuntimeError("ap_gemv_list failed")
+        return fn
+
     seq = inputs.decode_bit_sequence(64)
     results = {}
-    for name, fn in (("separate", issue), ("fused", issue_fused)):
+    for name, fn in (("separate", issue), ("fused", issue_fused), ("layer_list", issue_lists(layer_lists)),
+                     ("list32", issue_lists(wide_lists))):
         graphs = {}
         with torch.cuda.stream(cap):
             for b in range(3, 9):
@@ -164,7 +180,8 @@ def decode_step(args, np, torch, B, inputs, dev):
                       file=sys.stderr)
         results[name] = rows
     print(json.dumps(dict(metric="7B-shaped decode step latency by bit-width (224 batch-1 GEMVs per step; "
-                                 "'fused' = 128 launches: q,k,v | o | gate,up | down per layer)",
+                                 "'fused' = 128 launches: q,k,v | o | gate,up | down per layer; 'layer_list' = 32 "
+                                 "launches of one layer's 7 matrices; 'list32' = 7 launches of 32 matrices)",
                           unit="us/step", n_gpus=1, data="synthetic", sequence=seq, per_bit_width=results)))
 
 
@@ -179,6 +196,10 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 5],
                     help="benchmark configuration to run (default 2 = the headline workload)")
     ap.add_argument("--batch", type=int, default=1, help="batch size (exploration only; headline is 1)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="capture the independent calls of a step round robin on this many streams (parallel graph branches)")
+    ap.add_argument("--variant", type=int, default=0,
+                    help="kernel-selection override for A/B runs (ap_set_option AP_OPT_VARIANT; 0 = the dispatcher's choice)")
     ap.add_argument("--weights", choices=["uniform", "quantised"], default="uniform",
                     help="uniform: uniform random indices and random tables (headline recipe); quantised: "
                          "indices and tables from the incremental-upscaling quantiser on heavy-tailed weights "
@@ -227,22 +248,37 @@ def main():
         pm = B.ap_pack(idx, luts, device=dev)
         ncopies = max(2, min(COPIES, int(2.5e9 // pm.buf.numel())))
         copies = [pm] + [pm.clone() for _ in range(ncopies - 1)]
+        if args.variant:
+            for c in copies:
+                c.set_options(variant=args.variant)
         xd = torch.from_numpy(x).to(dev)
         yd = torch.empty((batch, M), dtype=torch.float16, device=dev)
         cases.append(dict(M=M, K=K, idx=idx, luts=luts, x=x, copies=copies, xd=xd, yd=yd))
     stream = torch.cuda.current_stream()
     sp = ctypes.c_void_p(stream.cuda_stream)
 
-    def issue_step(phase):
-        """The 18 calls of one step; `phase` selects which device copies they read."""
+    side = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else []
+    # one output buffer per call of a step: the calls are independent (no two write the same memory)
+    youts = {(b, i): torch.empty((batch, cs["M"]), dtype=torch.float16, device=dev) for b in bits for i, cs in enumerate(cases)}
+
+    def issue_step(phase, main=None):
+        """The 18 calls of one step; `phase` selects which device copies they read.  With side streams
+        the calls go round robin over them, forked from and joined to `main`."""
         c = phase * len(bits)
+        k = 0
+        for s_ in side:
+            s_.wait_stream(main)
         for b in bits:
-            for cs in cases:
+            for i, cs in enumerate(cases):
                 pm = cs["copies"][c % len(cs["copies"])]
-                st = B.lib.ap_gemv(pm.handle, b, cs["xd"].data_ptr(), cs["yd"].data_ptr(), batch, sp)
+                spk = ctypes.c_void_p(side[k % len(side)].cuda_stream) if side else sp
+                k += 1
+                st = B.lib.ap_gemv(pm.handle, b, cs["xd"].data_ptr(), youts[(b, i)].data_ptr(), batch, spk)
                 if st != 0:
                     raise RuntimeError("ap_gemv failed: %s" % B.strerror(st))
             c += 1
+        for s_ in side:
+            main.wait_stream(s_)
 
     step_bytes = sum(inputs.algorithmic_bytes(cs["M"], cs["K"], b, batch) for cs in cases for b in bits)
 
@@ -258,17 +294,17 @@ def main():
         with torch.cuda.stream(cap):
             sp = ctypes.c_void_p(cap.cuda_stream)
             for phase in range(COPIES):
-                issue_step(phase)          # eager warm-up on the capture stream
+                issue_step(phase, cap)     # eager warm-up on the capture stream
             cap.synchronize()
             for phase in range(COPIES):
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g, stream=cap):
-                    issue_step(phase)
+                    issue_step(phase, cap)
                 graphs.append(g)
             cycle_graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(cycle_graph, stream=cap):
                 for phase in range(COPIES):
-                    issue_step(phase)
+                    issue_step(phase, cap)
         sp = sp_save
         torch.cuda.synchronize()
 
@@ -277,7 +313,7 @@ def main():
         i = first
         while i < first + count:
             if graphs is None:
-                issue_step(i % COPIES)
+                issue_step(i % COPIES, stream)
                 i += 1
             elif i % COPIES == 0 and i + COPIES <= first + count:
                 cycle_graph.replay()

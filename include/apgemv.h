@@ -145,12 +145,12 @@ ap_status ap_set_option(ap_matrix *h, int option, int value);
 /*
  * Several GEMVs of the same bit-width in ONE launch: y_i = W_i,b * x_i for i < count (1..8), e.g. the
  * q/k/v or the gate/up projections of a decoder layer (Section 6.3 measures whole-model decoding,
- * where the per-launch cost of 224 small GEMVs per token matters).  All matrices must have the same
- * K and a table for b; M may differ; x_dev/y_dev may be shared or distinct per item (outputs must
- * not overlap).  At batch 1 and 2 each output is bit-identical to the one ap_gemv produces (same
+ * where the per-launch cost of 224 small GEMVs per token matters).  Every matrix needs a table for b;
+ * M may differ; at batch >= 2 all matrices must have the same K (AP_ERR_SHAPE otherwise), at batch 1
+ * any shapes go together; x_dev/y_dev may be shared or distinct per item (outputs must not overlap).
+ * At batch 1 and 2 each output is bit-identical to the one ap_gemv produces with default options (same
  * kernel per row group); at larger batches ap_gemv may pick another variant with a different
- * summation order, and both meet the same tolerance.  Same argument rules and error codes as
- * ap_gemv; AP_ERR_SHAPE if the row lengths differ.
+ * summation order, and both meet the same tolerance.  Same argument rules and error codes as ap_gemv.
  */
 typedef struct {
     const ap_matrix *h;
@@ -158,6 +158,27 @@ typedef struct {
     void *y_dev;       /* batch*M_i binary16 */
 } ap_gemv_item;
 ap_status ap_gemv_multi(const ap_gemv_item *items, int count, int b, int batch, void *stream);
+
+/*
+ * A work list of batch-1 products, each with its OWN bit-width, in as few launches as possible (one per
+ * 32 items): y_i = W_i,b_i * x_i.  This is the call for a decode step at per-layer mixed precision
+ * (Section 3.3: the bit-width is chosen at run time, per query; Section 6.3: end-to-end decoding is
+ * hundreds of small products per token): matrices of any shapes and bit-widths share a launch, so the
+ * per-launch start-up is paid once per list instead of once per matrix.
+ *   items[i].h      packed matrix;  items[i].b  its bit-width for this call (a table must be packed)
+ *   items[i].x_dev  device, K_i binary16, 16-byte aligned;  items[i].y_dev  device, M_i binary16
+ * count >= 1.  Outputs must not overlap each other, the inputs or the blobs; no item may depend on
+ * another item's output (all run concurrently).  Every item is checked before anything is enqueued;
+ * the status is that of the first bad item.  Each output is bit-identical to ap_gemv(h, b, x, y, 1)
+ * with default options.  Asynchronous on `stream`, allocates nothing, capturable in a graph.
+ */
+typedef struct {
+    const ap_matrix *h;
+    int b;
+    const void *x_dev;
+    void *y_dev;
+} ap_gemv_list_item;
+ap_status ap_gemv_list(const ap_gemv_list_item *items, int count, void *stream);
 
 /*
  * Dense binary16 weights of the b-bit model: w_dev[i*K + j] = C_b[i][ idx[i][j] >> (n-b) ], bit for

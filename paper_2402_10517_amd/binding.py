@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "AP_OK", 1: "AP_ERR_INVALID_ARG", 2: "AP_ERR_SHAPE", 3: "AP_E
                 7: "AP_ERR_HIP"}
 
 EXPORTS = ["ap_packed_size", "ap_pack_host", "ap_unpack_host", "ap_blob_lut_entry",
-           "ap_read_extent", "ap_pack", "ap_attach", "ap_set_option", "ap_unpack", "ap_gemv", "ap_gemv_multi", "ap_dequantize",
+           "ap_read_extent", "ap_pack", "ap_attach", "ap_set_option", "ap_unpack", "ap_gemv", "ap_gemv_multi", "ap_gemv_list", "ap_dequantize",
            "ap_gemm_workspace_size", "ap_gemm", "ap_gemm_static", "ap_quantize", "ap_probe_read", "ap_matrix_info",
            "ap_free", "ap_strerror"]
 
@@ -55,6 +55,7 @@ def _load():
     L.ap_unpack.argtypes = [vp, vp, vp]
     L.ap_gemv.argtypes = [vp, ci, vp, vp, ci, vp]
     L.ap_gemv_multi.argtypes = [vp, ci, ci, ci, vp]
+    L.ap_gemv_list.argtypes = [vp, ci, vp]
     L.ap_dequantize.argtypes = [vp, ci, vp, vp]
     L.ap_gemm_workspace_size.argtypes = [vp, psz]
     L.ap_gemm.argtypes = [vp, ci, vp, vp, ci, vp, sz, vp]
@@ -219,6 +220,29 @@ def make_items(triples):
         arr[i].x_dev = x.data_ptr()
         arr[i].y_dev = y.data_ptr()
     return arr
+
+
+class GemvListItem(ctypes.Structure):
+    _fields_ = [("h", ctypes.c_void_p), ("b", ctypes.c_int), ("x_dev", ctypes.c_void_p), ("y_dev", ctypes.c_void_p)]
+
+
+def make_list(quads):
+    """[(PackedMatrix, b, x tensor, y tensor), ...] -> ctypes array for ap_gemv_list."""
+    arr = (GemvListItem * len(quads))()
+    for i, (pm, b, x, y) in enumerate(quads):
+        arr[i].h = pm.handle.value if isinstance(pm.handle, ctypes.c_void_p) else pm.handle
+        arr[i].b = int(b)
+        arr[i].x_dev = x.data_ptr()
+        arr[i].y_dev = y.data_ptr()
+    return arr
+
+
+def ap_gemv_list(quads, stream=None):
+    """Batch-1 work list, one bit-width per item: quads = [(PackedMatrix, b, x, y), ...]; fills the y's."""
+    arr = make_list(quads)
+    sp, _ = _stream_ptr(stream)
+    _check(lib.ap_gemv_list(arr, len(quads), sp), "ap_gemv_list")
+    return [q[3] for q in quads]
 
 
 def ap_gemv_multi(triples, b, stream=None):

@@ -175,10 +175,60 @@ static ap_status fill_args(const ap_matrix *h, int b, GemvArgs *a)
     return AP_OK;
 }
 
+// Checks one item of a batch-1 list and fills its slot of the kernel argument.
+static ap_status fill_list_item(const ap_matrix *h, int b, const void *x_dev, void *y_dev, ListItem *li)
+{
+    GemvArgs a;
+    ap_status s = fill_args(h, b, &a);
+    if (s != AP_OK) return s;
+    if (!x_dev || !y_dev) return AP_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(x_dev) % 16 || reinterpret_cast<uintptr_t>(y_dev) % 2) return AP_ERR_INVALID_ARG;
+    li->slices = a.slices;
+    li->slice_bytes = a.slice_bytes;
+    li->lut = a.lut;
+    li->x = static_cast<const uint16_t *>(x_dev);
+    li->y = static_cast<uint16_t *>(y_dev);
+    li->M = a.M;
+    li->K = a.K;
+    li->b = b;
+    li->pad = 0;
+    return AP_OK;
+}
+
+extern "C" ap_status ap_gemv_list(const ap_gemv_list_item *items, int count, void *stream)
+{
+    if (!items || count < 1) return AP_ERR_INVALID_ARG;
+    ListItem probe;
+    for (int i = 0; i < count; ++i) { // every item is checked before anything is enqueued
+        ap_status s = fill_list_item(items[i].h, items[i].b, items[i].x_dev, items[i].y_dev, &probe);
+        if (s != AP_OK) return s;
+    }
+    for (int first = 0; first < count; first += kMaxListItems) {
+        ListArgs la;
+        std::memset(&la, 0, sizeof(la));
+        la.count = count - first < kMaxListItems ? count - first : kMaxListItems;
+        for (int i = 0; i < la.count; ++i)
+            fill_list_item(items[first + i].h, items[first + i].b, items[first + i].x_dev, items[first + i].y_dev,
+                           &la.item[i]);
+        if (launch_gemv_list(la, static_cast<hipStream_t>(stream)) != hipSuccess) return AP_ERR_HIP;
+    }
+    return AP_OK;
+}
+
 extern "C" ap_status ap_gemv_multi(const ap_gemv_item *items, int count, int b, int batch, void *stream)
 {
     if (!items || count < 1 || count > kMaxMulti) return AP_ERR_INVALID_ARG;
     if (batch < 1 || batch > AP_MAX_BATCH) return AP_ERR_BATCH;
+    if (batch == 1) { // any shapes: the list kernel, every item at bit-width b
+        ListArgs la;
+        std::memset(&la, 0, sizeof(la));
+        la.count = count;
+        for (int i = 0; i < count; ++i) {
+            ap_status s = fill_list_item(items[i].h, b, items[i].x_dev, items[i].y_dev, &la.item[i]);
+            if (s != AP_OK) return s;
+        }
+        return launch_gemv_list(la, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
+    }
     MultiArgs m;
     std::memset(&m, 0, sizeof(m));
     int total = 0;

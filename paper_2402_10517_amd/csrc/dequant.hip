@@ -26,8 +26,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 6))) voi
     const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
 
     StagedTable<B> st;
-    stage_tables_load<B>(st, lut, row0, M);
-    stage_tables_store<B>(st, tab, nat);
+    stage_tables_load<B>(st, lut, row0, M, blockDim.x);
+    stage_tables_store<B>(st, tab, nat, blockDim.x);
     __syncthreads();
     uint32_t one = 1;
     asm("" : "+v"(one));

@@ -87,6 +87,16 @@ template <int B> struct Table {
     }
 };
 
+// The 64-entry table of centroid pairs of the 3-bit path (Section 5.3 "Merging Table Lookups"): pair
+// index bit 2k is code bit k of the even slot, bit 2k+1 is code bit k of the odd slot.  Entry i6 of a
+// row = (centroid of the even slot's code, centroid of the odd slot's code), from the natural row.
+__device__ __forceinline__ uint32_t pair_entry(const uint16_t *nat_row, int i6)
+{
+    const int even = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
+    const int odd = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
+    return (uint32_t)nat_row[even] | ((uint32_t)nat_row[odd] << 16);
+}
+
 template <int ctrl> __device__ __forceinline__ float dpp_get(float v)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true));
@@ -119,15 +129,18 @@ template <int B> struct StagedTable {
 // All loads here are unconditional (indices clamped, unused results dropped or zeroed afterwards):
 // with no branch between them and the slice loads the compiler can count outstanding loads
 // exactly and waits for the table loads only.
+// `nth` = threads that take part (thread ids 0..nth-1; a multiple of 64, at least 64).
 template <int B>
-__device__ __forceinline__ void stage_tables_load(StagedTable<B> &st, const uint16_t *__restrict__ lut, int row0, int M)
+__device__ __forceinline__ void stage_tables_load(StagedTable<B> &st, const uint16_t *__restrict__ lut, int row0, int M,
+                                                  int nth)
 {
     using T = Table<B>;
     constexpr int TB = T::kRowBytes;
-    const int tid = threadIdx.x, nth = blockDim.x;
+    const int tid = threadIdx.x;
     const int last_row = M - 1 - row0; // >= 0
     if constexpr (B == 3) {
         // natural 8-entry rows: 4 rows x 4 dwords
+        static_assert(kRowsPerGroup * 4 <= 64, "one dword per thread of the first wave");
         const int i = tid < kRowsPerGroup * 4 ? tid : kRowsPerGroup * 4 - 1;
         const int r = i >> 2;
         const int rc = r < last_row ? r : last_row;
@@ -137,6 +150,7 @@ __device__ __forceinline__ void stage_tables_load(StagedTable<B> &st, const uint
         // stored order = LDS order, rows contiguous: 16-byte pieces
         constexpr int kPerRow = TB / 16;
         constexpr int kChunks = kRowsPerGroup * kPerRow;
+        static_assert(kChunks <= 2 * 64, "two rounds of at least 64 threads cover the tables");
         const u32x4 *src = reinterpret_cast<const u32x4 *>(lut + ((size_t)row0 << B));
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
@@ -151,6 +165,7 @@ __device__ __forceinline__ void stage_tables_load(StagedTable<B> &st, const uint
         // B = 4, 5: two stored entries per dword
         constexpr int kDwordsPerRow = (1 << B) / 2;
         constexpr int kDwords = kRowsPerGroup * kDwordsPerRow;
+        static_assert(kDwords <= 64, "one dword per thread of the first wave");
         const uint32_t *src = reinterpret_cast<const uint32_t *>(lut + ((size_t)row0 << B));
         const int i = tid < kDwords ? tid : kDwords - 1;
         const int r = i / kDwordsPerRow;
@@ -164,13 +179,13 @@ __device__ __forceinline__ void stage_tables_load(StagedTable<B> &st, const uint
 // behind the tables): a conditional store would pull its load down into the branch, behind the
 // slice loads.
 template <int B, int STRIDE = Table<B>::kRowBytes>
-__device__ __forceinline__ void stage_tables_store(const StagedTable<B> &st, uint8_t *tab, uint16_t *nat)
+__device__ __forceinline__ void stage_tables_store(const StagedTable<B> &st, uint8_t *tab, uint16_t *nat, int nth)
 {
     using T = Table<B>;
     constexpr int TB = T::kRowBytes;
     static_assert(STRIDE >= TB, "row stride in LDS");
     constexpr int kDummy = kRowsPerGroup * STRIDE; // byte offset of the dummy area inside tab
-    const int tid = threadIdx.x, nth = blockDim.x;
+    const int tid = threadIdx.x;
     if constexpr (B == 3) {
         // the 64-entry table of centroid pairs: pair index bit 2k is code bit k of the even slot,
         // bit 2k+1 is code bit k of the odd slot.
@@ -178,15 +193,10 @@ __device__ __forceinline__ void stage_tables_store(const StagedTable<B> &st, uin
                                                 : reinterpret_cast<uint32_t *>(tab + kDummy);
         *dst = st.v[0].x;
         __syncthreads();
-        // a thread's pair index is its lane (the block size is a multiple of 64): the two codes are
-        // formed once, the loop only walks the rows
+        // a thread's pair index is its lane (nth is a multiple of 64); the loop only walks the rows
         const int i6 = tid & 63;
-        const int a = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
-        const int c = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
-        for (int r = tid >> 6; r < kRowsPerGroup; r += nth >> 6) {
-            const uint32_t v = (uint32_t)nat[r * 8 + a] | ((uint32_t)nat[r * 8 + c] << 16);
-            *reinterpret_cast<uint32_t *>(tab + r * STRIDE + i6 * 4) = v;
-        }
+        for (int r = tid >> 6; r < kRowsPerGroup; r += nth >> 6)
+            *reinterpret_cast<uint32_t *>(tab + r * STRIDE + i6 * 4) = pair_entry(nat + r * 8, i6);
     } else if constexpr (B >= 6) {
         constexpr int kPerRow = TB / 16;
         constexpr int kChunks = kRowsPerGroup * kPerRow;
@@ -371,10 +381,7 @@ __device__ __forceinline__ void stage_tables_groups(uint8_t *tab, uint16_t *nat,
         __syncthreads();
         for (int i = tid; i < ng * kRowsPerGroup * 64; i += nth) {
             const int r = i >> 6, i6 = i & 63;
-            const int a = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
-            const int c = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
-            const uint32_t v = (uint32_t)nat[r * 8 + a] | ((uint32_t)nat[r * 8 + c] << 16);
-            *reinterpret_cast<uint32_t *>(tab + r * STRIDE + i6 * 4) = v;
+            *reinterpret_cast<uint32_t *>(tab + r * STRIDE + i6 * 4) = pair_entry(nat + r * 8, i6);
         }
     } else if constexpr (B >= 6) {
         constexpr int kPerRow = TB / 16;

@@ -25,7 +25,7 @@ namespace apgemv {
 template <int B, int NB, int MAXT>
 __device__ __forceinline__ void gemv_group(const uint8_t *__restrict__ slices, size_t slice_bytes,
                                            const uint16_t *__restrict__ lut, const uint16_t *__restrict__ x,
-                                           uint16_t *__restrict__ y, int M, int K, int batch, int g)
+                                           uint16_t *__restrict__ y, int M, int K, int batch, int g, int nwaves)
 {
     using T = Table<B>;
     constexpr int TB = T::kRowBytes;
@@ -35,7 +35,6 @@ __device__ __forceinline__ void gemv_group(const uint8_t *__restrict__ slices, s
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform, kept in an SGPR
-    const int nwaves = blockDim.x >> 6;
     const int row0 = g * kRowsPerGroup;
     const int chunks = K / kChunkSlots;
     const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
@@ -77,9 +76,9 @@ __device__ __forceinline__ void gemv_group(const uint8_t *__restrict__ slices, s
 
     int span = wave; // the launcher guarantees nwaves <= nspans
     StagedTable<B> st;
-    stage_tables_load<B>(st, lut, row0, M);
+    stage_tables_load<B>(st, lut, row0, M, nwaves * 64);
     issue_loads(span);
-    stage_tables_store<B>(st, tab, nat); // waits for the table loads only
+    stage_tables_store<B>(st, tab, nat, nwaves * 64); // waits for the table loads only
     __syncthreads();
     while (true) {
         if (active(span)) compute_unit<B, NB>(Q, X, tab, acc);
@@ -114,7 +113,7 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, (B <= 4
     const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
     const uint16_t *__restrict__ x, uint16_t *__restrict__ y, int M, int K, int batch)
 {
-    gemv_group<B, NB, MAXT>(slices, slice_bytes, lut, x, y, M, K, batch, blockIdx.x);
+    gemv_group<B, NB, MAXT>(slices, slice_bytes, lut, x, y, M, K, batch, blockIdx.x, blockDim.x >> 6);
 }
 
 // Several matrices with the same row length in one launch (the q/k/v or gate/up projections of
@@ -129,7 +128,95 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 6))) vo
     for (int i = 1; i < kMaxMulti; ++i)
         if (i < a.count && (int)blockIdx.x >= a.group_begin[i]) m = i;
     gemv_group<B, NB, MAXT>(a.slices[m], a.slice_bytes[m], a.lut[m], a.x[m], a.y[m], a.M[m], a.K, a.batch,
-                            (int)blockIdx.x - a.group_begin[m]);
+                            (int)blockIdx.x - a.group_begin[m], blockDim.x >> 6);
+}
+
+// A list of batch-1 products in one launch: matrices of any shapes, each with its own bit-width (the
+// projections of a decoder layer, possibly at per-layer mixed precision; Section 6.3 measures whole-model
+// decoding, where a launch per matrix costs more than the small matrices' own traffic).  Workgroup ->
+// (item, group of 4 rows) through the prefix sums of the group counts; the workgroup has as many waves
+// as the longest row of the list needs (at most 8), and waves beyond an item's span count retire before
+// the first barrier (a barrier counts the surviving waves only).  The work per group is that of
+// gemv_kernel with the same number of waves, so every output is bit-identical to a separate call.
+// B = the bit-width of every item, or 0 for a list of mixed bit-widths (one kernel then holds all six
+// code paths and the registers of the widest; lists of one bit-width get that bit-width's own kernel).
+template <int B, int MAXT>
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, (B == 3 || B == 4) ? 8 : 6))) void gemv_list_kernel(ListArgs a)
+{
+    int it = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxListItems; ++i)
+        if (i < a.count && (int)blockIdx.x >= a.group_begin[i]) it = i;
+    const ListItem &I = a.item[it];
+    const int K = I.K;
+    const int nspans = (K / kChunkSlots + kSpanLanes - 1) / kSpanLanes;
+    const int launched = blockDim.x >> 6;
+    const int nwaves = nspans < launched ? nspans : launched;
+    if ((int)(threadIdx.x >> 6) >= nwaves) return;
+    const int g = (int)blockIdx.x - a.group_begin[it];
+    if constexpr (B != 0) {
+        gemv_group<B, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves);
+    } else {
+        switch (I.b) {
+        case 3: gemv_group<3, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves); break;
+        case 4: gemv_group<4, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves); break;
+        case 5: gemv_group<5, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves); break;
+        case 6: gemv_group<6, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves); break;
+        case 7: gemv_group<7, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves); break;
+        default: gemv_group<8, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves); break;
+        }
+    }
+}
+
+// One launch for the items of `a` whose rows need `nw` waves.
+static hipError_t launch_list_class(const ListArgs &a, int nw, hipStream_t stream)
+{
+    constexpr int kMaxWaves = 8;
+    constexpr int T = 64 * kMaxWaves;
+    ListArgs sub;
+    sub.count = 0;
+    int total = 0, b = -1, max_nw = 1;
+    for (int i = 0; i < a.count; ++i) {
+        const int spans = (a.item[i].K / kChunkSlots + kSpanLanes - 1) / kSpanLanes;
+        const int w = spans < kMaxWaves ? spans : kMaxWaves;
+        if (w != nw) continue;
+        sub.item[sub.count] = a.item[i];
+        sub.group_begin[sub.count] = total;
+        ++sub.count;
+        total += padded_rows(a.item[i].M) / kRowsPerGroup;
+        if (w > max_nw) max_nw = w;
+        b = b < 0 || b == a.item[i].b ? a.item[i].b : 0;
+    }
+    if (sub.count == 0) return hipSuccess;
+    for (int i = sub.count; i < kMaxListItems; ++i) sub.group_begin[i] = 0x7fffffff;
+    const dim3 grid(total), block(64 * max_nw);
+    switch (b) {
+    case 3: hipLaunchKernelGGL((gemv_list_kernel<3, T>), grid, block, 0, stream, sub); break;
+    case 4: hipLaunchKernelGGL((gemv_list_kernel<4, T>), grid, block, 0, stream, sub); break;
+    case 5: hipLaunchKernelGGL((gemv_list_kernel<5, T>), grid, block, 0, stream, sub); break;
+    case 6: hipLaunchKernelGGL((gemv_list_kernel<6, T>), grid, block, 0, stream, sub); break;
+    case 7: hipLaunchKernelGGL((gemv_list_kernel<7, T>), grid, block, 0, stream, sub); break;
+    case 8: hipLaunchKernelGGL((gemv_list_kernel<8, T>), grid, block, 0, stream, sub); break;
+    default: hipLaunchKernelGGL((gemv_list_kernel<0, T>), grid, block, 0, stream, sub); break;
+    }
+    return hipGetLastError();
+}
+
+// The caller has checked every item (batch 1, 3 <= b <= 8).  Items are launched together per number of
+// waves their rows need (a workgroup has one wave per span, at most 8): a workgroup sized for the
+// longest row would hold wave slots for short rows that retire at once.
+hipError_t launch_gemv_list(ListArgs &a, hipStream_t stream)
+{
+    bool seen[9] = {};
+    for (int i = 0; i < a.count; ++i) {
+        const int spans = (a.item[i].K / kChunkSlots + kSpanLanes - 1) / kSpanLanes;
+        const int w = spans < 8 ? spans : 8;
+        if (seen[w]) continue;
+        seen[w] = true;
+        const hipError_t e = launch_list_class(a, w, stream);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // Variant for matrices with many rows and for batches: one workgroup owns up to kMaxRowGroups
@@ -195,10 +282,7 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(1, 6))) vo
         __syncthreads();
         for (int i = tid; i < ng * kRowsPerGroup * 64; i += nth) {
             const int r = i >> 6, i6 = i & 63;
-            const int a = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
-            const int c = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
-            const uint32_t v = (uint32_t)nat[r * 8 + a] | ((uint32_t)nat[r * 8 + c] << 16);
-            *reinterpret_cast<uint32_t *>(tab + r * TB + i6 * 4) = v;
+            *reinterpret_cast<uint32_t *>(tab + r * TB + i6 * 4) = pair_entry(nat + r * 8, i6);
         }
     } else if constexpr (B >= 6) {
         constexpr int kPerRow = TB / 16;

@@ -20,7 +20,7 @@ struct GemvArgs {
     int mfma_min_batch;    // 0 = default (3); batches below it use the ALU kernels; 9 = never
     int variant;           // AP_VARIANT_*: 0 = choose; 1 = never the matrix-core kernel with in-wave exchange;
                            // 3 = that kernel whenever the shape allows it (batch >= 2, K % 128 == 0);
-                           // 5 = the bank-per-lane kernel at batch 1, b >= 7
+                           // 5 = the bank-per-lane kernel at batch 1, b >= 7; 6 = one workgroup per row group at batch 1, 2
 };
 
 constexpr int kMaxMulti = 8;
@@ -35,7 +35,25 @@ struct MultiArgs { // passed by value as the kernel argument of a fused launch
     int count, K, batch;
 };
 
+// Work list of gemv_list_kernel, passed by value as its kernel argument (batch 1).
+constexpr int kMaxListItems = 32;
+struct ListItem {
+    const uint8_t *slices;
+    size_t slice_bytes;
+    const uint16_t *lut; // table of this item's bit-width
+    const uint16_t *x;
+    uint16_t *y;
+    int M, K, b;
+    int pad;
+};
+struct ListArgs {
+    ListItem item[kMaxListItems];
+    int group_begin[kMaxListItems]; // first workgroup of item i (filled in by the launcher)
+    int count;
+};
+
 hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream);
+hipError_t launch_gemv_list(ListArgs &a, hipStream_t stream);
 hipError_t launch_gemv_multi(const MultiArgs &a, int b, int total_groups, hipStream_t stream);
 hipError_t launch_dequantize(const GemvArgs &a, hipStream_t stream);
 hipError_t launch_probe_read(const void *dev_buf, size_t bytes, hipStream_t stream);

@@ -27,25 +27,25 @@ def test_config2_llama7b_shapes_every_row(B, M, K):
 
 
 @pytest.mark.parametrize("M,K", inputs.CONFIGS[3]["shapes"])
-def test_config3_llama13b_shapes_sampled_rows(B, M, K):
+def test_config3_llama13b_shapes_every_row(B, M, K):
     idx, luts, x = inputs.make_case(3, M, K)
     pm = B.ap_pack(idx, luts)
-    rows = np.unique(np.concatenate([np.arange(0, 8), np.arange(M - 8, M),
-                                     np.random.default_rng(M).integers(0, M, size=512)]))
     for b in ALL_BITS:
         y = run_gemv(pm, b, x)
-        check_against_oracle(y, idx, luts[b], b, x, rows=rows)
+        check_against_oracle(y, idx, luts[b], b, x)
     pm.close()
 
 
 @pytest.mark.parametrize("M,K", inputs.CONFIGS[5]["shapes"])
-def test_config5_llama70b_shapes_small_batch_sampled_rows(B, M, K):
+def test_config5_llama70b_shapes_every_row_at_batch_1_sampled_rows_at_batch_2_to_8(B, M, K):
     idx, luts, x = inputs.make_case(5, M, K, batch=8, sigma=0.01)
     pm = B.ap_pack(idx, luts)
     rows = np.unique(np.concatenate([np.arange(0, 4), np.arange(M - 4, M),
                                      np.random.default_rng(K).integers(0, M, size=256)]))
     for b in ALL_BITS:
-        for batch in (1, 2, 3, 4, 8):
+        y = run_gemv(pm, b, x[:1])
+        check_against_oracle(y, idx, luts[b], b, x[:1])
+        for batch in range(2, 9):
             y = run_gemv(pm, b, x[:batch])
             check_against_oracle(y, idx, luts[b], b, x[:batch], rows=rows)
     pm.close()
@@ -64,5 +64,27 @@ def test_config4_decode_step_bit_width_sequence(B):
             rows = np.random.default_rng(step).integers(0, idx.shape[0], size=64)
             y = run_gemv(pm, b, x)
             check_against_oracle(y, idx, luts[b], b, x, rows=rows)
+    for p in packed:
+        p[3].close()
+
+
+def test_config4_one_layer_as_a_mixed_precision_work_list(B):
+    """One decoder layer's seven matrices in ONE launch, each at its own bit-width: every row of every
+    output against the oracle, and bit for bit against separate ap_gemv calls."""
+    import torch
+    packed = []
+    for k, (M, K) in enumerate(inputs.DECODE_LAYER_SHAPES):
+        idx, luts, x = inputs.make_case(4, M, K, salt=k)
+        packed.append((idx, luts, x, B.ap_pack(idx, luts), torch.from_numpy(x).cuda()))
+    for bits in ([3, 4, 5, 6, 7, 8, 3], [8, 8, 3, 3, 5, 4, 7]):
+        quads = [(pm, b, xd, torch.full((1, pm.M), -3.0, dtype=torch.float16, device="cuda"))
+                 for (idx, luts, x, pm, xd), b in zip(packed, bits)]
+        B.ap_gemv_list(quads)
+        torch.cuda.synchronize()
+        for (idx, luts, x, pm, xd), (_, b, _, y) in zip(packed, quads):
+            check_against_oracle(y.cpu().numpy(), idx, luts[b], b, x)
+            sep = B.ap_gemv(pm, b, xd)
+            torch.cuda.synchronize()
+            assert torch.equal(sep, y)
     for p in packed:
         p[3].close()

@@ -228,17 +228,75 @@ def test_fused_launch_equals_separate_calls(B, batch):
                 if batch <= 2:   # same kernel as the single call: bit-identical
                     assert np.array_equal(y.cpu().numpy().view(np.uint16), sep.cpu().numpy().view(np.uint16))
                 check_against_oracle(y.cpu().numpy(), idx, luts[b], b, mats[0][2])
-    # row lengths must agree
+    # row lengths must agree at batch >= 2; at batch 1 any shapes share the launch
     idx, luts, x = inputs.make_case(20, 16, 512, batch=batch)
     other = B.ap_pack(idx, luts)
     y0 = torch.empty((batch, 64), dtype=torch.float16, device="cuda")
-    y1 = torch.empty((batch, 16), dtype=torch.float16, device="cuda")
-    with pytest.raises(B.ApError) as e:
-        B.ap_gemv_multi([(mats[0][3], shared_x, y0), (other, shared_x, y1)], 4)
-    assert e.value.status == 2
+    y1 = torch.full((batch, 16), -3.0, dtype=torch.float16, device="cuda")
+    x1 = torch.from_numpy(x).cuda()
+    if batch == 1:
+        B.ap_gemv_multi([(mats[0][3], shared_x, y0), (other, x1, y1)], 4)
+        torch.cuda.synchronize()
+        check_against_oracle(y1.cpu().numpy(), idx, luts[4], 4, x)
+        check_against_oracle(y0.cpu().numpy(), mats[0][0], mats[0][1][4], 4, mats[0][2])
+    else:
+        with pytest.raises(B.ApError) as e:
+            B.ap_gemv_multi([(mats[0][3], shared_x, y0), (other, x1, y1)], 4)
+        assert e.value.status == 2
     for m in mats:
         m[3].close()
     other.close()
+
+
+def test_work_list_mixed_shapes_and_bit_widths(B):
+    # one launch per 32 items: 40 items of 7 different shapes (1..9 spans, ragged spans, rows not a
+    # multiple of 4), each with its own bit-width; every output bit-identical to a separate ap_gemv
+    # call and within tolerance of the oracle; canaries between the outputs stay untouched
+    import torch
+    shapes = [(37, 96), (64, 2048 + 160), (130, 4096 + 32), (8, 512), (21, 3 * 2048), (5, 9 * 2048 + 32), (257, 1024)]
+    mats = []
+    for k, (M, K) in enumerate(shapes):
+        idx, luts, x = inputs.make_case(25, M, K, salt=k)
+        mats.append((idx, luts, x, B.ap_pack(idx, luts), torch.from_numpy(x).cuda()))
+    rng = np.random.default_rng(25)
+    picks = [(int(rng.integers(0, len(shapes))), int(rng.integers(3, 9))) for _ in range(40)]
+    guard = 16
+    total = sum(mats[m][3].M + guard for m, _ in picks) + guard
+    ybuf = torch.full((total,), -7.0, dtype=torch.float16, device="cuda")
+    quads, offs, off = [], [], guard
+    for m, b in picks:
+        M = mats[m][3].M
+        quads.append((mats[m][3], b, mats[m][4], ybuf[off:off + M]))
+        offs.append(off)
+        off += M + guard
+    B.ap_gemv_list(quads)
+    torch.cuda.synchronize()
+    out = ybuf.cpu().numpy()
+    mask = np.ones(total, dtype=bool)
+    for (m, b), o in zip(picks, offs):
+        idx, luts, x, pm, xd = mats[m]
+        y = out[o:o + pm.M].reshape(1, -1)
+        mask[o:o + pm.M] = False
+        sep = B.ap_gemv(pm, b, xd)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.view(np.uint16), sep.cpu().numpy().view(np.uint16)), (m, b)
+        check_against_oracle(y, idx, luts[b], b, x)
+    assert np.all(out[mask] == -7.0)
+    # a bad item anywhere in the list: its status, and nothing is enqueued
+    ybuf.fill_(-7.0)
+    bad = list(quads)
+    pm3 = B.ap_pack(mats[0][0], {3: mats[0][1][3]})
+    bad[35] = (pm3, 5, mats[0][4], ybuf[offs[35]:offs[35] + pm3.M])          # no table for b = 5
+    with pytest.raises(B.ApError) as e:
+        B.ap_gemv_list(bad)
+    assert e.value.status == 3
+    torch.cuda.synchronize()
+    assert np.all(ybuf.cpu().numpy() == -7.0)
+    assert B.lib.ap_gemv_list(None, 1, None) == 1
+    assert B.lib.ap_gemv_list(B.make_list(quads), 0, None) == 1
+    pm3.close()
+    for m in mats:
+        m[3].close()
 
 
 def test_graph_capture_and_replay_match_eager(B, tiny):
