@@ -28,7 +28,8 @@ typedef struct ap_matrix ap_matrix; /* opaque host-side handle of one packed mat
 typedef enum {
     AP_OK = 0,
     AP_ERR_INVALID_ARG = 1,      /* NULL pointer, misaligned buffer, bad handle */
-    AP_ERR_SHAPE = 2,            /* M < 1, K < 32 or K not a multiple of 32, sizes beyond 2^24 */
+    AP_ERR_SHAPE = 2,            /* M < 1, K < 32 or K not a multiple of 32, M or K beyond 2^24, more than
+                                    2^32 weights (rows counted up to a multiple of 4) */
     AP_ERR_BITS = 3,             /* n outside 3..8, b outside 3..n, or no table given for b */
     AP_ERR_INDEX_RANGE = 4,      /* an index >= 2^n */
     AP_ERR_BUFFER_TOO_SMALL = 5, /* destination smaller than ap_packed_size */

@@ -22,6 +22,11 @@ __device__ __forceinline__ uint32_t rotl_c(uint32_t v, int r)
 }
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Buffer descriptors of raw (untyped, unstrided) device memory: word 3 = 32-bit data format, no swizzle;
+// the range check is not relied upon (num_records = 2^32 - 1, callers clamp their own offsets).
+constexpr uint32_t kBufferRsrcWord3 = 0x00020000u;
+constexpr int kBufferNonTemporal = 2; // cache-policy bits of a buffer load: streaming data, read once
+
 // d = (m & a) | (~m & b) with a constant mask: one v_bfi_b32 (the mask sits in an SGPR)
 __device__ __forceinline__ uint32_t bitsel(uint32_t m, uint32_t a, uint32_t b)
 {

@@ -41,29 +41,31 @@ __device__ __forceinline__ void gemv_group(const uint8_t *__restrict__ slices, s
 
     u32x4 Q[B];
     u32x4 X[NB][4];
-    // Loads of the lane's slice words and activations for one span (Section 5.2 step 1).
+    // Loads of the lane's slice words and activations for one span (Section 5.2 step 1), as buffer
+    // loads: wave-uniform base and offset in scalar registers, one per-lane byte offset for all of
+    // them, so that no vector operation is spent on addresses.  The slice descriptor starts at this
+    // group's first unit of slice 0; slice s is s * slice_bytes further (below 4 GiB: the packed
+    // format limits a matrix to 2^32 weights).
+    const __amdgpu_buffer_rsrc_t srsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(slices + (size_t)g * chunks * 16), 0, 0xffffffffu, kBufferRsrcWord3);
     auto issue_loads = [&](int span) {
         const int rem = chunks - span * kSpanLanes;
         const int nl = rem < kSpanLanes ? rem : kSpanLanes;
-        {
-            // Lanes past the end of a ragged last span load what the last valid lane loads (and are
-            // masked out of the compute): no branch around the loads.
-            // wave-uniform base + 32-bit lane offset: the loads use the scalar-base address form
-            const uint8_t *sbase = slices + ((size_t)g * chunks + (size_t)span * kSpanLanes) * 16;
-            const uint32_t loff = (uint32_t)(lane < nl ? lane : nl - 1) * 16u;
+        // Lanes past the end of a ragged last span load what the last valid lane loads (and are
+        // masked out of the compute): no branch around the loads.
+        const uint32_t loff = (uint32_t)(lane < nl ? lane : nl - 1) * 16u;
+        const uint32_t sspan = (uint32_t)span * (kSpanLanes * 16u);
 #pragma unroll
-            for (int s = 0; s < B; ++s)
-                Q[s] = __builtin_nontemporal_load(
-                    reinterpret_cast<const u32x4 *>(sbase + (size_t)s * slice_bytes + loff));
+        for (int s = 0; s < B; ++s)
+            Q[s] = __builtin_amdgcn_raw_buffer_load_b128(srsrc, loff, sspan + (uint32_t)s * (uint32_t)slice_bytes, kBufferNonTemporal);
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int xr = nb < batch ? nb : batch - 1;
-                const uint8_t *xbase =
-                    reinterpret_cast<const uint8_t *>(x + (size_t)xr * K + (size_t)span * kSpanCols);
+        for (int nb = 0; nb < NB; ++nb) {
+            const int xr = nb < batch ? nb : batch - 1;
+            const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<uint16_t *>(x + (size_t)xr * K + (size_t)span * kSpanCols), 0, 0xffffffffu, kBufferRsrcWord3);
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    X[nb][t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)(t * 16 * nl) + loff);
-            }
+            for (int t = 0; t < 4; ++t)
+                X[nb][t] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, loff, (uint32_t)(t * 16 * nl), 0);
         }
     };
     auto active = [&](int span) { return lane < chunks - span * kSpanLanes; };

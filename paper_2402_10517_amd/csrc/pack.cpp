@@ -18,6 +18,8 @@ ap_status check_shape(int M, int K, int n)
     if (n < AP_MIN_BITS || n > AP_MAX_BITS) return AP_ERR_BITS;
     if (M < 1 || K < kChunkSlots || K % kChunkSlots != 0) return AP_ERR_SHAPE;
     if (M > (1 << 24) || K > (1 << 24)) return AP_ERR_SHAPE;
+    // the kernels address the slices of a row group with 32-bit offsets: 7 * slice_bytes < 4 GiB
+    if ((unsigned long long)padded_rows(M) * (unsigned long long)K > (1ull << 32)) return AP_ERR_SHAPE;
     return AP_OK;
 }
 
@@ -271,7 +273,7 @@ extern "C" const char *ap_strerror(ap_status s)
     switch (s) {
     case AP_OK: return "ok";
     case AP_ERR_INVALID_ARG: return "invalid argument";
-    case AP_ERR_SHAPE: return "unsupported shape (need M >= 1, K a multiple of 32)";
+    case AP_ERR_SHAPE: return "unsupported shape (need M >= 1, K a multiple of 32, M and K at most 2^24, at most 2^32 weights)";
     case AP_ERR_BITS: return "bit-width not supported for this matrix";
     case AP_ERR_INDEX_RANGE: return "index value does not fit the parent bit-width";
     case AP_ERR_BUFFER_TOO_SMALL: return "buffer smaller than ap_packed_size";

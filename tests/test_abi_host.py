@@ -143,6 +143,8 @@ def test_error_paths_before_any_device_work():
     L = B.lib
     assert L.ap_packed_size(0, 64, 8, FULL_MASK, ctypes.byref(sz)) == 2      # M < 1
     assert L.ap_packed_size(8, 48, 8, FULL_MASK, ctypes.byref(sz)) == 2      # K % 32
+    assert L.ap_packed_size(1 << 20, 1 << 12, 8, FULL_MASK, ctypes.byref(sz)) == 0   # 2^32 weights: the limit
+    assert L.ap_packed_size((1 << 20) + 1, 1 << 12, 8, FULL_MASK, ctypes.byref(sz)) == 2
     assert L.ap_packed_size(8, 64, 9, FULL_MASK, ctypes.byref(sz)) == 3      # n
     assert L.ap_packed_size(8, 64, 2, 1 << 2, ctypes.byref(sz)) == 3
     assert L.ap_packed_size(8, 64, 6, B.lut_mask([3, 7]), ctypes.byref(sz)) == 3   # table above n
