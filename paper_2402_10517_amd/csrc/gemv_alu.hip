@@ -78,8 +78,14 @@ __device__ __forceinline__ void gemv_group(const uint8_t *__restrict__ slices, s
 
     int span = wave; // the launcher guarantees nwaves <= nspans
     StagedTable<B> st;
+    // A wave issues all its requests in one burst at raised priority: the memory pipeline serves a
+    // compute unit's requests in order, so waves whose bursts do not interleave receive their data
+    // one after the other and start computing while the later ones are still being served, instead
+    // of all finishing their last slice at the end of the stream together.
+    __builtin_amdgcn_s_setprio(3);
     stage_tables_load<B>(st, lut, row0, M, nwaves * 64);
     issue_loads(span);
+    __builtin_amdgcn_s_setprio(0);
     stage_tables_store<B>(st, tab, nat, nwaves * 64); // waits for the table loads only
     __syncthreads();
     while (true) {
