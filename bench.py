@@ -192,7 +192,7 @@ def decode_step_rows(np, torch, B, inputs, dev, modes, replays):
     return results, seq
 
 
-def per_call_rows(torch, B, inputs, dev, config, batches, bits, sp, variant=0, detail=False):
+def per_call_rows(torch, B, inputs, dev, config, batches, bits, sp, variant=0, detail=False, waves=0):
     """Single ap_gemv calls of every shape of `config`: back-to-back launches over rotating device
     copies between two events (median of 3 runs); the average includes the dispatch gap between
     dependent launches, so it is at least the kernel's own duration."""
@@ -207,6 +207,9 @@ def per_call_rows(torch, B, inputs, dev, config, batches, bits, sp, variant=0, d
         if variant:
             for c in copies:
                 c.set_options(variant=variant)
+        if waves:
+            for c in copies:
+                c.set_options(waves=waves)
         for batch in batches:
             xd = torch.from_numpy(x[:batch].copy()).to(dev)
             yd = torch.empty((batch, M), dtype=torch.float16, device=dev)
@@ -266,6 +269,7 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 5],
                     help="exploration: per-call timing of this configuration only (2 = the full default run)")
     ap.add_argument("--batch", type=int, default=1, help="exploration: batch size of --config 3|5 runs")
+    ap.add_argument("--waves", type=int, default=0, help="exploration: waves per row group (ap_set_option AP_OPT_WAVES_PER_GROUP)")
     ap.add_argument("--variant", type=int, default=0,
                     help="kernel-selection override for A/B runs (ap_set_option AP_OPT_VARIANT; 0 = the dispatcher's choice)")
     ap.add_argument("--weights", choices=["uniform", "quantised"], default="uniform",
@@ -305,7 +309,8 @@ def main():
         large_batch(args, np, torch, B, inputs, dev)
         return
     if args.config != 2:
-        rows = per_call_rows(torch, B, inputs, dev, args.config, [args.batch], bits, sp, args.variant, detail=True)
+        rows = per_call_rows(torch, B, inputs, dev, args.config, [args.batch], bits, sp, args.variant, detail=True,
+                             waves=args.waves)
         print(json.dumps(dict(metric="exploration: single ap_gemv calls", config=args.config, batch=args.batch,
                               variant=args.variant, per_call=rows)))
         return

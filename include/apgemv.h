@@ -34,7 +34,8 @@ typedef enum {
     AP_ERR_INDEX_RANGE = 4,      /* an index >= 2^n */
     AP_ERR_BUFFER_TOO_SMALL = 5, /* destination smaller than ap_packed_size */
     AP_ERR_BATCH = 6,            /* batch outside 1..8 */
-    AP_ERR_HIP = 7               /* a HIP runtime call or kernel launch failed */
+    AP_ERR_HIP = 7,              /* a HIP runtime call or kernel launch failed */
+    AP_ERR_NO_MEMORY = 8         /* host memory (a handle, the pinned staging buffer) could not be allocated */
 } ap_status;
 
 #define AP_MIN_BITS 3
@@ -86,7 +87,9 @@ ap_status ap_read_extent(int M, int K, int n, unsigned lut_mask, int b, size_t *
  *             handle; the library never allocates device memory for model data
  *   stream    the upload is enqueued on it and has completed when the call returns
  *   out       receives the handle (host object; release with ap_free)
- * The host arrays may be released after return.
+ * The host arrays may be released after return.  The packed form is staged in pinned host memory that
+ * the library keeps and reuses for later ap_pack / ap_unpack calls (as large as the largest matrix
+ * handled so far; calls are serialised on it); AP_ERR_NO_MEMORY if it cannot be had.
  */
 ap_status ap_pack(const uint8_t *idx_host, int M, int K, int n, const uint16_t *const luts_host[9],
                   void *dev_buf, size_t dev_buf_bytes, void *stream, ap_matrix **out);
@@ -246,7 +249,8 @@ ap_status ap_probe_read(const void *dev_buf, size_t bytes, void *stream);
 /* Shape and supported bit-widths of a handle; any output pointer may be NULL. */
 ap_status ap_matrix_info(const ap_matrix *h, int *M, int *K, int *n, unsigned *lut_mask);
 
-/* Releases the host handle only; the device buffer stays with the caller. NULL is allowed. */
+/* Releases the host handle only; the device buffer stays with the caller. NULL is allowed.  A handle
+ * must not be passed to any call after ap_free (the checks of a handle cannot detect that). */
 void ap_free(ap_matrix *h);
 
 /* Static, never NULL. */

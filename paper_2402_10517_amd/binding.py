@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libapgemv.so")
 AP_OK = 0
 STATUS_NAMES = {0: "AP_OK", 1: "AP_ERR_INVALID_ARG", 2: "AP_ERR_SHAPE", 3: "AP_ERR_BITS",
                 4: "AP_ERR_INDEX_RANGE", 5: "AP_ERR_BUFFER_TOO_SMALL", 6: "AP_ERR_BATCH",
-                7: "AP_ERR_HIP"}
+                7: "AP_ERR_HIP", 8: "AP_ERR_NO_MEMORY"}
 
 EXPORTS = ["ap_packed_size", "ap_pack_host", "ap_unpack_host", "ap_blob_lut_entry",
            "ap_read_extent", "ap_pack", "ap_attach", "ap_set_option", "ap_unpack", "ap_gemv", "ap_gemv_multi", "ap_gemv_list", "ap_dequantize",

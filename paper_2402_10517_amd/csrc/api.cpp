@@ -2,8 +2,8 @@
 #include <hip/hip_runtime_api.h>
 
 #include <cstring>
+#include <mutex>
 #include <new>
-#include <vector>
 
 #include "dense_gemm.h"
 #include "handle.h"
@@ -11,6 +11,37 @@
 #include "pack.h"
 
 using namespace apgemv;
+
+// Pinned host staging for uploads and downloads of packed matrices: one buffer per process, grown to
+// the largest size asked for and kept (pinned memory transfers at about twice the rate of pageable
+// memory, and allocating it per call would cost more than the transfer).  Calls are serialised on it.
+namespace {
+struct Staging {
+    std::mutex lock;
+    void *ptr = nullptr;
+    size_t capacity = 0;
+    // with `lock` held
+    uint8_t *reserve(size_t bytes)
+    {
+        if (bytes <= capacity) return static_cast<uint8_t *>(ptr);
+        if (ptr) (void)hipHostFree(ptr);
+        ptr = nullptr;
+        capacity = 0;
+        if (hipHostMalloc(&ptr, bytes, hipHostMallocDefault) != hipSuccess) {
+            ptr = nullptr;
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        capacity = bytes;
+        return static_cast<uint8_t *>(ptr);
+    }
+};
+Staging &staging_buffer()
+{
+    static Staging *s = new Staging; // never destroyed: no HIP call during process teardown
+    return *s;
+}
+} // namespace
 
 static void default_tuning(ap_matrix *h)
 {
@@ -35,23 +66,29 @@ extern "C" ap_status ap_pack(const uint8_t *idx_host, int M, int K, int n,
     s = make_header(M, K, n, mask, &hdr);
     if (s != AP_OK) return s;
     if (dev_buf_bytes < hdr.total_bytes) return AP_ERR_BUFFER_TOO_SMALL;
-
-    std::vector<uint8_t> staging;
-    try {
-        staging.resize(hdr.total_bytes);
-    } catch (const std::bad_alloc &) {
-        return AP_ERR_INVALID_ARG;
-    }
-    s = ap_pack_host(idx_host, M, K, n, luts_host, staging.data(), staging.size());
+    s = check_index_range(idx_host, M, K, n); // the last check that needs no HIP call
     if (s != AP_OK) return s;
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (hipMemcpyAsync(dev_buf, staging.data(), hdr.total_bytes, hipMemcpyHostToDevice, st) != hipSuccess)
-        return AP_ERR_HIP;
-    if (hipStreamSynchronize(st) != hipSuccess) return AP_ERR_HIP;
-
     ap_matrix *h = new (std::nothrow) ap_matrix;
-    if (!h) return AP_ERR_INVALID_ARG;
+    if (!h) return AP_ERR_NO_MEMORY;
+    {
+        Staging &sb = staging_buffer();
+        std::lock_guard<std::mutex> guard(sb.lock);
+        uint8_t *staging = sb.reserve(hdr.total_bytes);
+        if (!staging) {
+            delete h;
+            return AP_ERR_NO_MEMORY;
+        }
+        s = ap_pack_host(idx_host, M, K, n, luts_host, staging, hdr.total_bytes);
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        if (s == AP_OK && (hipMemcpyAsync(dev_buf, staging, hdr.total_bytes, hipMemcpyHostToDevice, st) != hipSuccess ||
+                           hipStreamSynchronize(st) != hipSuccess))
+            s = AP_ERR_HIP;
+        if (s != AP_OK) {
+            delete h;
+            return s;
+        }
+    }
     h->tag = kHandleTag;
     h->hdr = hdr;
     h->dev = static_cast<uint8_t *>(dev_buf);
@@ -73,7 +110,7 @@ extern "C" ap_status ap_attach(void *dev_buf, size_t dev_buf_bytes, void *stream
     ap_status s = validate_header(&hdr, dev_buf_bytes);
     if (s != AP_OK) return s;
     ap_matrix *h = new (std::nothrow) ap_matrix;
-    if (!h) return AP_ERR_INVALID_ARG;
+    if (!h) return AP_ERR_NO_MEMORY;
     h->tag = kHandleTag;
     h->hdr = hdr;
     h->dev = static_cast<uint8_t *>(dev_buf);
@@ -113,20 +150,17 @@ extern "C" ap_status ap_unpack(const ap_matrix *h, uint8_t *idx_host_out, void *
 {
     if (!handle_ok(h) || !idx_host_out) return AP_ERR_INVALID_ARG;
     const size_t bytes = h->hdr.slice_off + (size_t)h->hdr.n * h->hdr.slice_bytes;
-    std::vector<uint8_t> staging;
-    try {
-        staging.resize(bytes);
-    } catch (const std::bad_alloc &) {
-        return AP_ERR_INVALID_ARG;
-    }
+    Staging &sb = staging_buffer();
+    std::lock_guard<std::mutex> guard(sb.lock);
+    uint8_t *staging = sb.reserve(bytes);
+    if (!staging) return AP_ERR_NO_MEMORY;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (hipMemcpyAsync(staging.data(), h->dev, bytes, hipMemcpyDeviceToHost, st) != hipSuccess)
-        return AP_ERR_HIP;
+    if (hipMemcpyAsync(staging, h->dev, bytes, hipMemcpyDeviceToHost, st) != hipSuccess) return AP_ERR_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) return AP_ERR_HIP;
     BlobHeader hdr;
-    std::memcpy(&hdr, staging.data(), sizeof(hdr));
+    std::memcpy(&hdr, staging, sizeof(hdr));
     if (std::memcmp(&hdr, &h->hdr, sizeof(hdr)) != 0) return AP_ERR_INVALID_ARG;
-    unpack_slices(staging.data(), hdr, idx_host_out);
+    unpack_slices(staging, hdr, idx_host_out);
     return AP_OK;
 }
 

@@ -48,6 +48,10 @@ bool dense_gemm_f16(const void *w_dev, const void *x_dev, void *y_dev, int M, in
 {
     Blas &b = blas();
     if (!b.ok) return false;
+    // one rocBLAS handle for the process: the stream it is bound to and the call that uses it must not
+    // be separated by another thread's call
+    static std::mutex call_lock;
+    std::lock_guard<std::mutex> guard(call_lock);
     if (b.set_stream(b.handle, stream) != rocblas_status_success) return false;
     // Column-major view: Y^T (M x batch, ld M) = W (op T on the K x M view, ld K) * X^T (K x batch, ld K)
     const float alpha = 1.0f, beta = 0.0f;

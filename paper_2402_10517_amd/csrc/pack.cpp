@@ -31,6 +31,16 @@ ap_status check_mask(int n, unsigned lut_mask)
     return AP_OK;
 }
 
+ap_status check_index_range(const uint8_t *idx, int M, int K, int n)
+{
+    if (n >= 8) return AP_OK;
+    const size_t total = (size_t)M * K;
+    const unsigned limit = 1u << n;
+    for (size_t i = 0; i < total; ++i)
+        if (idx[i] >= limit) return AP_ERR_INDEX_RANGE;
+    return AP_OK;
+}
+
 ap_status make_header(int M, int K, int n, unsigned lut_mask, BlobHeader *h)
 {
     ap_status s = check_shape(M, K, n);
@@ -205,12 +215,8 @@ extern "C" ap_status ap_pack_host(const uint8_t *idx, int M, int K, int n,
     s = make_header(M, K, n, mask, &h);
     if (s != AP_OK) return s;
     if (blob_bytes < h.total_bytes) return AP_ERR_BUFFER_TOO_SMALL;
-    if (n < 8) {
-        const size_t total = (size_t)M * K;
-        const unsigned limit = 1u << n;
-        for (size_t i = 0; i < total; ++i)
-            if (idx[i] >= limit) return AP_ERR_INDEX_RANGE;
-    }
+    s = check_index_range(idx, M, K, n);
+    if (s != AP_OK) return s;
     uint8_t *out = static_cast<uint8_t *>(blob);
     std::memset(out, 0, h.total_bytes);
     std::memcpy(out, &h, sizeof(h));
@@ -279,6 +285,7 @@ extern "C" const char *ap_strerror(ap_status s)
     case AP_ERR_BUFFER_TOO_SMALL: return "buffer smaller than ap_packed_size";
     case AP_ERR_BATCH: return "batch outside 1..8";
     case AP_ERR_HIP: return "HIP runtime call or kernel launch failed";
+    case AP_ERR_NO_MEMORY: return "host memory could not be allocated";
     }
     return "unknown status";
 }

@@ -24,8 +24,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_strerror_is_static_text_for_every_status():
-    for s in range(0, 9):
+    for s in range(0, 10):
         assert isinstance(B.strerror(s), str) and B.strerror(s)
+    assert len({B.strerror(s) for s in range(0, 9)}) == 9        # one text per status code
 
 
 def test_packed_size_is_n_bits_per_weight_plus_tables():
@@ -168,6 +169,10 @@ def test_error_paths_before_any_device_work():
     assert L.ap_pack(idx.ctypes.data, M, K, 8, arr, fake_dev, 16, None, ctypes.byref(h)) == 5
     assert L.ap_pack(idx.ctypes.data, M, K, 8, arr, ctypes.c_void_p(0x10004), 1 << 20, None,
                      ctypes.byref(h)) == 1                                    # misaligned buffer
+    arr6, keep6 = B._lut_array({b: t for b, t in _luts(M).items() if b <= 6})
+    bad = idx.copy()
+    bad[3, 5] = 64                                                            # does not fit a 6-bit parent
+    assert L.ap_pack(bad.ctypes.data, M, K, 6, arr6, fake_dev, 1 << 20, None, ctypes.byref(h)) == 4
     assert L.ap_gemv_multi(None, 1, 4, 1, None) == 1
     assert L.ap_dequantize(None, 4, fake_dev, None) == 1
     assert L.ap_gemm_workspace_size(None, ctypes.byref(sz)) == 1

@@ -107,10 +107,19 @@ def test_integer_table_pins_bit_order_end_to_end(B, b):
     pm.close()
 
 
+# kernel families for the adversarial inputs: the dispatcher's own choice, the one-row-per-lane
+# matrix-core kernel for every b, the matrix-core kernel with in-wave exchange; the last two need
+# K % 128 == 0 and batch >= 3 / >= 2, which the shapes below satisfy
+FAMILIES = [dict(), dict(mfma_min_batch=-3), dict(variant=3)]
+
+
+@pytest.mark.parametrize("family", range(len(FAMILIES)))
+@pytest.mark.parametrize("batch", [1, 3, 5, 8])
 @pytest.mark.parametrize("b", ALL_BITS)
-def test_adversarial_tables(B, b):
-    M, K = 48, 2048 + 32
-    idx, luts, x = inputs.make_case(16, M, K)
+def test_adversarial_tables(B, b, batch, family):
+    M, K = 48, 2048 + 128
+    assert K % 128 == 0                                   # so that the matrix-core kernels are reachable
+    idx, luts, x = inputs.make_case(16, M, K, batch=batch)
     rng = np.random.default_rng(b)
     E = 1 << b
     lut = luts[b].copy()
@@ -122,25 +131,28 @@ def test_adversarial_tables(B, b):
     lut[3, E - 1] = np.float16(-65504.0)
     idx[5, :] = 0xA5                                      # a row whose indices are all equal
     xs = (x.astype(np.float32) * 1e-3).astype(np.float16) # keeps 65504 * x finite
-    pm = B.ap_pack(idx, {b: lut})
+    pm = B.ap_pack(idx, {b: lut}).set_options(**FAMILIES[family])
     for xv in (xs, np.zeros_like(x)):
         y = run_gemv(pm, b, xv)
         check_against_oracle(y, idx, lut, b, xv)
     pm.close()
 
 
-@pytest.mark.parametrize("batch", [1, 2, 8])
+@pytest.mark.parametrize("family", range(len(FAMILIES)))
+@pytest.mark.parametrize("batch", [1, 2, 3, 5, 8])
 @pytest.mark.parametrize("b", ALL_BITS)
-def test_subnormal_centroids_are_not_flushed(B, b, batch):
+def test_subnormal_centroids_are_not_flushed(B, b, batch, family):
     # every centroid is a binary16 subnormal (k * 2^-24), activations are large: a path that
-    # flushed subnormal inputs to zero would return 0 where the result is of order 10
-    M, K = 20, 2048 + 64
+    # flushed subnormal inputs to zero (the matrix instructions included) would return 0 where the
+    # result is of order 10
+    M, K = 20, 2048 + 128
+    assert K % 128 == 0
     rng = np.random.default_rng(100 + b)
     idx = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
     lut = (rng.integers(1, 1024, size=(M, 1 << b)).astype(np.uint16)).view(np.float16)
     x = np.full((batch, K), 512.0, dtype=np.float16)
     x[:, ::3] = -256.0
-    pm = B.ap_pack(idx, {b: lut})
+    pm = B.ap_pack(idx, {b: lut}).set_options(**FAMILIES[family])
     y = run_gemv(pm, b, x)
     assert np.all(np.abs(y.astype(np.float64)) > 0.05)
     check_against_oracle(y, idx, lut, b, x)

@@ -11,8 +11,7 @@ import oracle
 from paper_2402_10517_amd import inputs
 
 pytestmark = pytest.mark.gpu
-REL_TOL = 1e-3
-ABS_FLOOR = 2.0 ** -25
+from gpu_util import tolerance
 
 
 @pytest.fixture(scope="module")
@@ -49,7 +48,7 @@ def test_static_gemm_matches_gemm_on_two_calls_in_a_row(B):
         for b in bits:
             got, ref = _both(B, torch, pm, b, x)
             _, mag = oracle.gemv(idx, luts[b], b, x)
-            tol = REL_TOL * mag + ABS_FLOOR
+            tol = tolerance(mag)
             err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
             assert np.all(np.isfinite(got))
             assert np.all(err <= 2 * tol), float(np.max(err / tol))   # each side is within tol of the exact value
