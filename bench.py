@@ -192,7 +192,7 @@ def decode_step_rows(np, torch, B, inputs, dev, modes, replays):
     return results, seq
 
 
-def per_call_rows(torch, B, inputs, dev, config, batches, bits, sp, variant=0, detail=False, waves=0):
+def per_call_rows(torch, B, inputs, dev, config, batches, bits, sp, variant=0, detail=False, waves=0, mfma_min_batch=0):
     """Single ap_gemv calls of every shape of `config`: back-to-back launches over rotating device
     copies between two events (median of 3 runs); the average includes the dispatch gap between
     dependent launches, so it is at least the kernel's own duration."""
@@ -210,6 +210,9 @@ def per_call_rows(torch, B, inputs, dev, config, batches, bits, sp, variant=0, d
         if waves:
             for c in copies:
                 c.set_options(waves=waves)
+        if mfma_min_batch:
+            for c in copies:
+                c.set_options(mfma_min_batch=mfma_min_batch)
         for batch in batches:
             xd = torch.from_numpy(x[:batch].copy()).to(dev)
             yd = torch.empty((batch, M), dtype=torch.float16, device=dev)
@@ -270,6 +273,10 @@ def main():
                     help="exploration: per-call timing of this configuration only (2 = the full default run)")
     ap.add_argument("--batch", type=int, default=1, help="exploration: batch size of --config 3|5 runs")
     ap.add_argument("--waves", type=int, default=0, help="exploration: waves per row group (ap_set_option AP_OPT_WAVES_PER_GROUP)")
+    ap.add_argument("--mfma-min-batch", type=int, default=0,
+                    help="exploration: smallest batch for the one-row-per-lane matrix-core kernel (AP_OPT_MFMA_MIN_BATCH; 9 = never)")
+    ap.add_argument("--per-call-only", action="store_true",
+                    help="exploration: only the single-call timing of --config (2 included) at --batch")
     ap.add_argument("--variant", type=int, default=0,
                     help="kernel-selection override for A/B runs (ap_set_option AP_OPT_VARIANT; 0 = the dispatcher's choice)")
     ap.add_argument("--weights", choices=["uniform", "quantised"], default="uniform",
@@ -308,9 +315,9 @@ def main():
     if args.large_batch:
         large_batch(args, np, torch, B, inputs, dev)
         return
-    if args.config != 2:
+    if args.config != 2 or args.per_call_only:
         rows = per_call_rows(torch, B, inputs, dev, args.config, [args.batch], bits, sp, args.variant, detail=True,
-                             waves=args.waves)
+                             waves=args.waves, mfma_min_batch=args.mfma_min_batch)
         print(json.dumps(dict(metric="exploration: single ap_gemv calls", config=args.config, batch=args.batch,
                               variant=args.variant, per_call=rows)))
         return

@@ -131,7 +131,10 @@ ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int
  *                             with in-wave exchange; AP_VARIANT_EXCHANGE = that kernel whenever the
  *                             shape allows (batch >= 2, K % 128 == 0); AP_VARIANT_BANK_PER_LANE = at
  *                             batch 1, b >= 7: the kernel in which every lane looks up its own LDS
- *                             bank column (8 copies of each row's table) instead of the default
+ *                             bank column (8 copies of each row's table) instead of the default;
+ *                             AP_VARIANT_PAIR / AP_VARIANT_NO_PAIR = at batch 1: the kernel with two
+ *                             groups of 4 rows per workgroup whenever every span has its own wave
+ *                             (2048 < K <= 16384) / never (the default)
  * AP_ERR_INVALID_ARG for an unknown option or a value outside its range.
  */
 typedef enum {
@@ -144,6 +147,8 @@ typedef enum {
 #define AP_VARIANT_NO_EXCHANGE 1
 #define AP_VARIANT_EXCHANGE 3
 #define AP_VARIANT_BANK_PER_LANE 5
+#define AP_VARIANT_PAIR 7
+#define AP_VARIANT_NO_PAIR 8
 ap_status ap_set_option(ap_matrix *h, int option, int value);
 
 /*

@@ -35,10 +35,14 @@ hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream)
             return launch_matrix_exchange(a, stream);
     }
     // The first matrix-core kernel (one row per lane): batch 3..8 at b >= 6 when the row length allows
-    // it; at b <= 5 the four rows' small tables of a block share LDS banks and it is slower
-    // (mfma_min_batch: tuning override; a negative value also lifts the b limit).
+    // it; at b <= 5 the four rows' small tables of a block share LDS banks and it is slower.  Matrices
+    // with fewer than 2048 groups of rows stay on the ALU kernels: measured on 4096x4096 and 4096x11008
+    // at batch 3, 4, 8 the ALU kernels are level or up to 30 % faster there (the device is not full,
+    // and a call is bound by latency, not by the multiply-accumulates the matrix cores take over).
+    // (mfma_min_batch: tuning override, also of the size rule; a negative value lifts the b limit too.)
     const int min_batch = a.mfma_min_batch > 0 ? a.mfma_min_batch : a.mfma_min_batch < 0 ? -a.mfma_min_batch : 3;
-    if (a.batch >= min_batch && a.K % 128 == 0 && (B >= 6 || a.mfma_min_batch < 0))
+    const bool big_enough = a.mfma_min_batch != 0 || padded_rows(a.M) / kRowsPerGroup >= 2048;
+    if (a.batch >= min_batch && a.K % 128 == 0 && big_enough && (B >= 6 || a.mfma_min_batch < 0))
         return launch_matrix_row_per_lane(a, stream);
     return launch_alu(a, stream);
 }

@@ -116,6 +116,90 @@ __device__ __forceinline__ void gemv_group(const uint8_t *__restrict__ slices, s
     }
 }
 
+// Two consecutive groups of 4 rows per workgroup, batch 1, one wave per span: every wave requests the
+// slice words of both groups up front (twice the bytes in flight per wave slot: at 3 to 5 bits one
+// group per wave leaves HBM waiting at full occupancy), loads its activations once for both, and the
+// table staging and the two barriers are shared.  Per row the arithmetic and its order are those of
+// gemv_group, so the outputs are bit-identical.  `gp` = index of the pair; with an odd number of
+// groups the last workgroup computes the last group twice and stores it once.
+template <int B, int MAXT>
+__device__ __forceinline__ void gemv_group_pair(const uint8_t *__restrict__ slices, size_t slice_bytes,
+                                                const uint16_t *__restrict__ lut, const uint16_t *__restrict__ x,
+                                                uint16_t *__restrict__ y, int M, int K, int gp, int nwaves)
+{
+    using T = Table<B>;
+    constexpr int TB = T::kRowBytes;
+    constexpr int R = 2;
+    __shared__ __attribute__((aligned(16))) uint8_t tab[R][kRowsPerGroup * TB + 16]; // + dummy area
+    __shared__ __attribute__((aligned(16))) uint16_t nat[R][kRowsPerGroup * 8];
+    __shared__ float red[MAXT / 64][R][4][kRowsPerGroup]; // [wave][group][DPP row][lane & 3]
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int groups = (M + kRowsPerGroup - 1) / kRowsPerGroup;
+    const int g0 = gp * R;
+    const bool both = g0 + 1 < groups;
+    const int gofs = both ? 1 : 0; // second group of the pair, as an offset from the first
+    const int chunks = K / kChunkSlots;
+    const int span = wave; // the launcher gives every span its own wave
+    const int rem = chunks - span * kSpanLanes;
+    const int nl = rem < kSpanLanes ? rem : kSpanLanes;
+    const bool active = lane < nl;
+    const uint32_t loff = (uint32_t)(active ? lane : nl - 1) * 16u;
+
+    const __amdgpu_buffer_rsrc_t srsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(slices + (size_t)g0 * chunks * 16), 0, 0xffffffffu, kBufferRsrcWord3);
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(x + (size_t)span * kSpanCols), 0, 0xffffffffu, kBufferRsrcWord3);
+    StagedTable<B> st[R];
+    u32x4 Q[R][B];
+    u32x4 X[1][4];
+    __builtin_amdgcn_s_setprio(3); // one uninterrupted burst of requests per wave (see gemv_group)
+#pragma unroll
+    for (int rg = 0; rg < R; ++rg) stage_tables_load<B>(st[rg], lut, (g0 + rg * gofs) * kRowsPerGroup, M, nwaves * 64);
+#pragma unroll
+    for (int rg = 0; rg < R; ++rg) {
+        const uint32_t sunit = (uint32_t)(rg * gofs) * (uint32_t)chunks * 16u + (uint32_t)span * (kSpanLanes * 16u);
+#pragma unroll
+        for (int s = 0; s < B; ++s)
+            Q[rg][s] = __builtin_amdgcn_raw_buffer_load_b128(srsrc, loff, sunit + (uint32_t)s * (uint32_t)slice_bytes, kBufferNonTemporal);
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) X[0][t] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, loff, (uint32_t)(t * 16 * nl), 0);
+    __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+    for (int rg = 0; rg < R; ++rg) stage_tables_store<B>(st[rg], tab[rg], nat[rg], nwaves * 64);
+    __syncthreads();
+#pragma unroll
+    for (int rg = 0; rg < R; ++rg) {
+        float acc[1][kRowsPerGroup] = {{0.f, 0.f, 0.f, 0.f}};
+        if (active) compute_unit<B, 1>(Q[rg], X, tab[rg], acc);
+        const float c = reduce4_in_dpp_rows(acc[0], lane);
+        if ((lane & 15) >= 12) red[wave][rg][lane >> 4][lane & 3] = c;
+    }
+    __syncthreads();
+    if (threadIdx.x < R * kRowsPerGroup) {
+        const int rg = threadIdx.x / kRowsPerGroup, r = threadIdx.x % kRowsPerGroup;
+        const int cls = ((r & 1) << 1) | (r >> 1); // lane & 3 that holds row r
+        float s = 0.f;
+        for (int w = 0; w < nwaves; ++w)
+            for (int d = 0; d < 4; ++d) s += red[w][rg][d][cls];
+        const int row = (g0 + rg) * kRowsPerGroup + r;
+        if ((rg == 0 || both) && row < M) {
+            const __half h = __float2half_rn(s);
+            y[row] = __builtin_bit_cast(uint16_t, h);
+        }
+    }
+}
+
+template <int B, int MAXT>
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, B <= 4 ? 8 : 6))) void gemv_pair_kernel(
+    const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
+    const uint16_t *__restrict__ x, uint16_t *__restrict__ y, int M, int K)
+{
+    gemv_group_pair<B, MAXT>(slices, slice_bytes, lut, x, y, M, K, blockIdx.x, blockDim.x >> 6);
+}
+
 template <int B, int NB, int MAXT>
 __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, (B <= 4 && NB == 1) ? 8 : 6))) void gemv_kernel(
     const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
@@ -345,6 +429,7 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(1, 6))) vo
     }
 }
 
+
 template <int B, int NB>
 static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
 {
@@ -369,6 +454,16 @@ static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
                            dim3(64 * nspans), 0, stream, a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M,
                            a.K, a.batch, rg);
         return hipGetLastError();
+    }
+    // Two row groups per workgroup at batch 1: on request only.  On 28672x8192 it measured within the
+    // run-to-run spread of the kernel with one group per workgroup (+-5 % either way, by bit-width), and
+    // smaller matrices need every workgroup they can get (11008x4096: 10 to 30 % slower).
+    if constexpr (NB == 1) {
+        if (nw == nspans && nspans >= 2 && a.waves_per_group == 0 && a.row_groups_per_wg < 0 && a.variant == 7) {
+            hipLaunchKernelGGL((gemv_pair_kernel<B, kMaxThreads>), dim3((groups + 1) / 2), dim3(64 * nw), 0, stream,
+                               a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M, a.K);
+            return hipGetLastError();
+        }
     }
     hipLaunchKernelGGL((gemv_kernel<B, NB, kMaxThreads>), dim3(groups), dim3(64 * nw), 0, stream,
                        a.slices, a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);

@@ -20,7 +20,8 @@ struct GemvArgs {
     int mfma_min_batch;    // 0 = default (3); batches below it use the ALU kernels; 9 = never
     int variant;           // AP_VARIANT_*: 0 = choose; 1 = never the matrix-core kernel with in-wave exchange;
                            // 3 = that kernel whenever the shape allows it (batch >= 2, K % 128 == 0);
-                           // 5 = the bank-per-lane kernel at batch 1, b >= 7; 6 = one workgroup per row group at batch 1, 2
+                           // 5 = the bank-per-lane kernel at batch 1, b >= 7;
+                           // 7 / 8 = two row groups per workgroup at batch 1 whenever possible / never
 };
 
 constexpr int kMaxMulti = 8;

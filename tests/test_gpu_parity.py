@@ -217,6 +217,21 @@ def test_bank_per_lane_variant(B, b):
         pm.close()
 
 
+@pytest.mark.parametrize("b", ALL_BITS)
+def test_two_row_groups_per_workgroup_variant(B, b):
+    # forced (the dispatcher uses it on large matrices only): 2..8 spans, a ragged last span, an odd
+    # number of row groups (the last workgroup holds one group), rows not a multiple of 4; the outputs
+    # are bit-identical to the kernel with one group per workgroup
+    for (M, K) in [(70, 2048 + 160), (129, 4096 + 32), (66, 3 * 2048), (10, 5 * 2048 + 736), (4, 8 * 2048), (37, 2048 + 32)]:
+        idx, luts, x = inputs.make_case(26, M, K, bit_widths=[b])
+        pm = B.ap_pack(idx, luts).set_options(variant=B.VARIANT_PAIR)
+        y = run_gemv(pm, b, x)
+        check_against_oracle(y, idx, luts[b], b, x)
+        pm.set_options(variant=B.VARIANT_NO_PAIR)
+        assert np.array_equal(y.view(np.uint16), run_gemv(pm, b, x).view(np.uint16))
+        pm.close()
+
+
 @pytest.mark.parametrize("batch", [1, 2, 8])
 def test_fused_launch_equals_separate_calls(B, batch):
     import torch
@@ -387,7 +402,7 @@ def test_output_canaries_and_sparse_support(B):
 def test_option_values_are_checked(B, tiny):
     _, _, _, pm = tiny
     L = B.lib
-    for opt, bad in ((0, 9), (0, -1), (1, 0), (1, 5), (2, 10), (3, 2), (3, 7), (9, 0)):
+    for opt, bad in ((0, 9), (0, -1), (1, 0), (1, 5), (2, 10), (3, 2), (3, 6), (3, 9), (9, 0)):
         assert L.ap_set_option(pm.handle, opt, bad) == 1, (opt, bad)
     for opt, good, default in ((0, 2, 0), (1, 1, -1), (2, 9, 0), (3, 1, 0)):
         assert L.ap_set_option(pm.handle, opt, good) == 0
