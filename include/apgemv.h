@@ -134,7 +134,10 @@ ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void *y_dev, int
  *                             bank column (8 copies of each row's table) instead of the default;
  *                             AP_VARIANT_PAIR / AP_VARIANT_NO_PAIR = at batch 1: the kernel with two
  *                             groups of 4 rows per workgroup whenever every span has its own wave
- *                             (2048 < K <= 16384) / never (the default)
+ *                             (2048 < K <= 16384) / never (the default);
+ *                             AP_VARIANT_TILE / AP_VARIANT_TILE2 = at batch >= 2, K % 256 == 0: the
+ *                             matrix-core kernel that works on tiles of 16 rows, with one / two
+ *                             tiles per workgroup
  * AP_ERR_INVALID_ARG for an unknown option or a value outside its range.
  */
 typedef enum {
@@ -149,6 +152,8 @@ typedef enum {
 #define AP_VARIANT_BANK_PER_LANE 5
 #define AP_VARIANT_PAIR 7
 #define AP_VARIANT_NO_PAIR 8
+#define AP_VARIANT_TILE 9
+#define AP_VARIANT_TILE2 10
 ap_status ap_set_option(ap_matrix *h, int option, int value);
 
 /*

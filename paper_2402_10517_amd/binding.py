@@ -30,6 +30,7 @@ EXPORTS = ["ap_packed_size", "ap_pack_host", "ap_unpack_host", "ap_blob_lut_entr
 OPTIONS = {"waves": 0, "row_groups": 1, "mfma_min_batch": 2, "variant": 3}
 VARIANT_AUTO, VARIANT_NO_EXCHANGE, VARIANT_EXCHANGE, VARIANT_BANK_PER_LANE = 0, 1, 3, 5
 VARIANT_PAIR, VARIANT_NO_PAIR = 7, 8
+VARIANT_TILE, VARIANT_TILE2 = 9, 10
 
 
 class ApError(RuntimeError):

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libapgemv.so")
-SOURCES = ["gemv_alu.hip", "gemv_quad.hip", "gemv_matrix.hip", "dequant.hip", "gemm_static.hip", "dispatch.cpp", "api.cpp", "pack.cpp",
+SOURCES = ["gemv_alu.hip", "gemv_quad.hip", "gemv_matrix.hip", "gemv_tile.hip", "dequant.hip", "gemm_static.hip", "dispatch.cpp", "api.cpp", "pack.cpp",
            "dense_gemm.cpp", "quantize.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -138,7 +138,8 @@ extern "C" ap_status ap_set_option(ap_matrix *h, int option, int value)
         return AP_OK;
     case AP_OPT_VARIANT:
         if (value != AP_VARIANT_AUTO && value != AP_VARIANT_NO_EXCHANGE && value != AP_VARIANT_EXCHANGE &&
-            value != AP_VARIANT_BANK_PER_LANE && value != AP_VARIANT_PAIR && value != AP_VARIANT_NO_PAIR)
+            value != AP_VARIANT_BANK_PER_LANE && value != AP_VARIANT_PAIR && value != AP_VARIANT_NO_PAIR &&
+            value != AP_VARIANT_TILE && value != AP_VARIANT_TILE2)
             return AP_ERR_INVALID_ARG;
         h->variant = value;
         return AP_OK;

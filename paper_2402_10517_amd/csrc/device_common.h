@@ -23,7 +23,8 @@ __device__ __forceinline__ uint32_t rotl_c(uint32_t v, int r)
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Buffer descriptors of raw (untyped, unstrided) device memory: word 3 = 32-bit data format, no swizzle;
-// the range check is not relied upon (num_records = 2^32 - 1, callers clamp their own offsets).
+// weight loads do not rely on the range check (num_records = 2^32 - 1, callers clamp their own
+// offsets); the tile kernel's activation loads do (a lane offset >= num_records reads zeros).
 constexpr uint32_t kBufferRsrcWord3 = 0x00020000u;
 constexpr int kBufferNonTemporal = 2; // cache-policy bits of a buffer load: streaming data, read once
 
@@ -362,6 +363,7 @@ __device__ __forceinline__ void compute_unit(const u32x4 (&Q)[B], const u32x4 (&
 }
 
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 

@@ -13,8 +13,21 @@ hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream)
     // and 8 copies of every table; measured slower than the shared-table kernel on every Llama shape
     // (b = 8: 8.2 / 17.7 / 19.6 us against 6.8 / 12.0 / 12.7 us on the 7B shapes), so only on request.
     if (a.batch == 1 && B >= 7 && a.variant == 5) return launch_quad(a, stream);
-    // Which kernel for batch >= 2 was settled by measurement on the 70B shapes (8192x8192, 28672x8192,
-    // 8192x28672; all b):
+    // The matrix-core kernel on tiles of 16 rows (K % 256 == 0).  Measured on the 13B and 70B shapes at
+    // batch 2, 3, 4, 6, 8 against the kernels below: at batch >= 5 it wins on every matrix with at least
+    // 1024 groups of rows (5 to 49 %, most at small b and long rows; level at b = 8 on the 13B shapes);
+    // at batch 3 and 4 it wins by 5 to 30 % on rows of 16384 columns or more and is level elsewhere; at
+    // batch 2, and on 1024 x 8192 at every batch, the ALU kernels are faster.
+    // variant: 9 / 10 = this kernel with one / two tiles per workgroup whenever the shape allows; any
+    // other tuning override keeps the call away from it.
+    if (a.batch >= 2 && a.K % 256 == 0) {
+        const int groups = padded_rows(a.M) / kRowsPerGroup;
+        const bool tuned = a.row_groups_per_wg >= 0 || a.mfma_min_batch != 0 || a.waves_per_group != 0;
+        const bool pays = a.variant == 0 && !tuned && groups >= 1024 && (a.batch >= 5 || (a.batch >= 3 && a.K >= 16384));
+        if (a.variant == 9 || a.variant == 10 || pays) return launch_matrix_tile(a, stream);
+    }
+    // What is left for batch >= 2 (K not a multiple of 256, smaller matrices, batch 2..4) was settled by
+    // measurement on the 70B shapes (8192x8192, 28672x8192, 8192x28672; all b):
     //  * batch 2: the plain kernel (one group of rows per workgroup) wins everywhere;
     //  * batch 5..8 with >= 2048 groups of rows: the matrix-core kernel with in-wave exchange, every b
     //    (up to 24 % faster than the ALU kernels at b <= 5, level at b = 8);

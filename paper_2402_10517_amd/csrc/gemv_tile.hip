@@ -1,0 +1,306 @@
+// Small-batch kernel (batch 2..8) that feeds v_mfma_f32_16x16x32_f16 from the dequantising lanes
+// (Section 6.2 "Matrix-Matrix Multiplication Performance": the paper's kernel runs batches on the
+// ordinary ALUs and slows down by up to 2x at batch 8).
+//
+// In that instruction lane l supplies A[l % 16][8 (l / 16) .. + 7] and B[8 (l / 16) .. + 7][l % 16] and
+// receives D[4 (l / 16) .. + 3][l % 16].  With A = weights and B = activations this fixes who owns
+// what: lane (i, kg) = (l % 16, l / 16) dequantises row i of a tile of 16 rows, 8 columns per
+// instruction; the multiply-accumulate cost does not depend on the batch.
+//   * A wave works on octets of chunks (8 chunks = 256 columns of the tile's 16 rows): two quads of
+//     chunks, lane group kg taking chunk kg of the first and chunk 4 + kg of the second.
+//   * Every load instruction reads whole 128-byte lines in lane order.  A slice load covers 2 row groups
+//     x 8 chunks x 4 rows (lane 32 p + 4 c + r: group p, chunk c, row r), two loads per slice and tile;
+//     one v_permlane16_swap turns the pair into the words of the first and of the second quad (all 4
+//     row groups each), and one ds_bpermute per word moves a word to the lane that dequantises it
+//     (lane 16 kg + 4 g + r: group g, row r).  Loaded directly in that order, every 4 lanes would touch
+//     another cache line and a line would be requested again while it is still in flight.
+//   * The activations of a run of an octet are 128 contiguous bytes per batch row: lane 8 n + p loads
+//     the 16 bytes of batch row n for chunk p, so one instruction covers 8 batch rows line by line (a
+//     lane-per-row order costs one cache access per lane).  Four ds_bpermute per run move them to the
+//     lanes of the matrix instruction: lane (i, kg) takes batch row i % 8, chunk 4 (i / 8) + kg; lanes
+//     i < 8 then hold the first quad's operand, and a rotation by 8 lanes inside each group of 16
+//     brings them the second quad's.  Output columns i >= 8 are never stored, so what the matrix
+//     instruction gets there does not matter; batch rows that do not exist read zeros (their buffer
+//     offset is out of range: no memory traffic).
+//   * One instruction takes one run of 8 consecutive columns: their indices are the bytes of the
+//     merged words of the run's even and odd slots, the activations the lane's 16 bytes of that run.
+//   * The LDS serves 32 lanes per clock, here 16 rows x 2 lane groups, so every (row, lane group
+//     parity) gets a bank of its own: each row's table is stored twice, entry v (the masked index
+//     byte) of row i for lane groups of parity c is the low half of the dword at
+//     (v << s) | (c << 6) | (i << 2), with s such that the lowest index bit lands on address bit 7;
+//     no two lanes of a clock share a bank.  The 3-bit path keeps its 64-entry table of centroid
+//     pairs, one pair per dword.
+// Requires K % 256 == 0 (an octet is entirely inside or outside a ragged last span) and batch <= 8.
+#include "device_common.h"
+#include "launchers.h"
+
+namespace apgemv {
+
+template <int B> struct TileTable {
+    static constexpr bool kPair = (B == 3);
+    static constexpr uint32_t kMask = kPair ? 0xFCu : Table<B>::addr_mask(); // index bits inside a merged byte
+    static constexpr int kLow = (kMask & 1) ? 0 : (kMask & 2) ? 1 : 2;       // lowest of them
+    static constexpr int kShift = 7 - kLow;
+    static constexpr int kTileBytes = (int)((kMask >> kLow) + 1) << 7; // 16 rows x 2 copies x 4 bytes per entry
+    // masked byte value of the entry stored at position p of a row (lut_stored_pos order; pair index for B = 3)
+    __device__ static constexpr uint32_t byte_of(uint32_t p)
+    {
+        return kPair ? p << 2 : B == 4 ? (((p & 8u) << 3) | ((p & 7u) << 2)) : p << kLow;
+    }
+};
+
+template <int B, int R, int MAXT>
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 5))) void gemv_tile_kernel(
+    const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
+    const uint16_t *__restrict__ x, uint16_t *__restrict__ y, int M, int K, int batch)
+{
+    using TT = TileTable<B>;
+    constexpr int kTileRows = 16, kTileGroups = kTileRows / kRowsPerGroup;
+    // the tables during the main loop, then the waves' partial sums [wave][tile][row][batch row]
+    constexpr int kTabBytes = R * TT::kTileBytes, kRedBytes = (MAXT / 64) * R * kTileRows * 16 * 4;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[kTabBytes > kRedBytes ? kTabBytes : kRedBytes];
+    uint8_t *tab = smem;
+    float(*red)[R][kTileRows][16] = reinterpret_cast<float(*)[R][kTileRows][16]>(smem);
+
+    const int tid = threadIdx.x, nth = blockDim.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nwaves = nth >> 6;
+    const int i = lane & 15;  // row of a tile this lane dequantises; output column (batch row) it receives
+    const int kg = lane >> 4; // its 8 columns of every instruction; its chunk of every quad of chunks
+    const int groups = (M + kRowsPerGroup - 1) / kRowsPerGroup;
+    const int g0 = blockIdx.x * (R * kTileGroups);
+    const int row0 = g0 * kRowsPerGroup;
+    const int chunks = K / kChunkSlots;
+    const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
+
+    // ---- tables of the R tiles into LDS (rows past the matrix repeat the last row; never stored).
+    // Thread e writes copy (e / 16) % 2 of row e % 16: the 32 lanes of an LDS clock hit 32 different banks
+    // (with one row per wave every lane of a store would land in the same bank).
+    {
+        const int srow = tid & 15, scopy = (tid >> 4) & 1;
+        constexpr int kPerRow = TT::kPair ? 64 : (1 << B) / 2; // pair entries, or dwords of two entries
+        for (int e = tid >> 5; e < R * kPerRow; e += nth >> 5) {
+            const int tile = e / kPerRow, d = e % kPerRow;
+            const int row = row0 + tile * kTileRows + srow < M ? row0 + tile * kTileRows + srow : M - 1;
+            uint8_t *base = tab + tile * TT::kTileBytes + ((srow << 2) | (scopy << 6));
+            if constexpr (TT::kPair) {
+                *reinterpret_cast<uint32_t *>(base + (TT::byte_of(d) << TT::kShift)) = pair_entry(lut + (size_t)row * 8, d);
+            } else {
+                const uint32_t v = reinterpret_cast<const uint32_t *>(lut + ((size_t)row << B))[d];
+                *reinterpret_cast<uint16_t *>(base + (TT::byte_of(2 * d) << TT::kShift)) = (uint16_t)v;
+                *reinterpret_cast<uint16_t *>(base + (TT::byte_of(2 * d + 1) << TT::kShift)) = (uint16_t)(v >> 16);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- per-lane offsets of the slice loads: lane 32 p + 4 c + r loads row r of row group 2 half + p of
+    // the tile, chunk c of the octet
+    const int lp = lane >> 5, lc = (lane >> 2) & 7, lr = lane & 3;
+    const __amdgpu_buffer_rsrc_t srsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(slices + (size_t)g0 * chunks * 16), 0, 0xffffffffu, kBufferRsrcWord3);
+    uint32_t soff_lane[R][2];
+#pragma unroll
+    for (int tile = 0; tile < R; ++tile)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            int rg = tile * kTileGroups + 2 * half + lp;
+            if (g0 + rg >= groups) rg = groups - 1 - g0; // past the matrix: the last group again (never stored)
+            soff_lane[tile][half] = (uint32_t)(rg * chunks + lc) * 16u + (uint32_t)lr * 4u;
+        }
+    // After the swap of 16-lane rows, lane 16 p + 4 c + r of the first (second) word holds row r, chunk c
+    // (4 + c) of the row group at position p of the order 0, 2, 1, 3; this lane dequantises row i & 3 of
+    // row group i >> 2, chunk kg (4 + kg).
+    const int bperm_src = (((((i >> 2) & 1) << 1 | (i >> 3)) << 4) | (kg << 2) | (i & 3)) << 2; // byte address of the source lane
+    // activations: lane 8 n + p loads batch row n, chunk p of the octet; the descriptor ends with the last
+    // batch row, and lanes of rows past the batch carry an offset beyond it (batch * K * 2 < 2^31; valid
+    // lanes stay below the end with any scalar offset).  This lane then takes batch row i & 7, chunk
+    // 4 (i >> 3) + kg.
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(x), 0, (uint32_t)batch * (uint32_t)K * 2u, kBufferRsrcWord3);
+    const uint32_t xoff_lane =
+        (lane >> 3) < batch ? (uint32_t)(lane >> 3) * (uint32_t)K * 2u + (uint32_t)(lane & 7) * 16u : 0x80000000u;
+    const int xperm_src = (((i & 7) << 3) | ((i >> 3) << 2) | kg) << 2; // byte address of the source lane
+    const uint32_t rowbase = ((uint32_t)i << 2) | ((uint32_t)(kg & 1) << 6);
+
+    float4_t acc[R][2]; // one accumulator per quad of an octet: independent chains of matrix instructions
+#pragma unroll
+    for (int tile = 0; tile < R; ++tile) acc[tile][0] = acc[tile][1] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    // Octet o of a row = chunks 8 o .. 8 o + 7 (span o / 8); the waves split the row's pairs of octets
+    // evenly.  The loads of an octet are issued before the arithmetic of the octet before it (two
+    // register sets).  Every pass of the loop issues the same loads and has no exit in the middle, so the
+    // wait before the arithmetic leaves exactly the newer loads in flight: a row with an odd number of
+    // octets gets one more whose activations are read as zeros (offset out of range), and the loads
+    // issued in the last pass for the pass after it repeat a valid octet and are dropped.
+    auto issue = [&](int o, bool real, u32x4 (&X)[4], uint32_t (&Q)[R][2][B]) {
+        const int span = o >> 3, oi = o & 7;
+        const int rem = chunks - span * kSpanLanes;
+        const int nl = rem < kSpanLanes ? rem : kSpanLanes;
+        const uint32_t xs = (uint32_t)span * (kSpanCols * 2u) + (uint32_t)oi * 128u;
+        const uint32_t xoff = real ? xoff_lane : 0x80000000u;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) X[t] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, xoff, xs + (uint32_t)(t * 16 * nl), 0);
+        const uint32_t soct = (uint32_t)o * 128u;
+#pragma unroll
+        for (int tile = 0; tile < R; ++tile)
+#pragma unroll
+            for (int s = 0; s < B; ++s)
+#pragma unroll
+                for (int half = 0; half < 2; ++half)
+                    Q[tile][half][s] = __builtin_amdgcn_raw_buffer_load_b32(srsrc, soff_lane[tile][half],
+                                                                            soct + (uint32_t)s * (uint32_t)slice_bytes, kBufferNonTemporal);
+    };
+    auto compute = [&](const u32x4 (&Xl)[4], const uint32_t (&Q)[R][2][B]) {
+        u32x4 X[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) X[t][d] = (uint32_t)__builtin_amdgcn_ds_bpermute(xperm_src, (int)Xl[t][d]);
+#pragma unroll
+        for (int tile = 0; tile < R; ++tile) {
+            const uint8_t *tt = tab + tile * TT::kTileBytes;
+            uint32_t W[2][8]; // [quad of the octet]
+            {
+                uint32_t q[2][B];
+#pragma unroll
+                for (int s = 0; s < B; ++s) {
+                    const auto sw = __builtin_amdgcn_permlane16_swap(Q[tile][0][s], Q[tile][1][s], false, false);
+                    q[0][s] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm_src, (int)sw[0]);
+                    q[1][s] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm_src, (int)sw[1]);
+                }
+                merge_words<B>(q[0], W[0]);
+                merge_words<B>(q[1], W[1]);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                uint32_t P[2][4]; // packed centroid pairs: P[h][j] = columns 2j, 2j + 1 of run t, quad h
+                if constexpr (TT::kPair) {
+                    uint32_t ad[2][4];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const uint32_t v = W[h][2 * t];
+                        ad[h][0] = (byte_and<0>(v, TT::kMask) << TT::kShift) | rowbase;
+                        ad[h][1] = (byte_and<1>(v, TT::kMask) << TT::kShift) | rowbase;
+                        ad[h][2] = (byte_and<2>(v, TT::kMask) << TT::kShift) | rowbase;
+                        ad[h][3] = (byte_and<3>(v, TT::kMask) << TT::kShift) | rowbase;
+                    }
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) P[h][j] = *reinterpret_cast<const uint32_t *>(tt + ad[h][j]);
+                } else {
+                    uint32_t ae[2][4], ao[2][4];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const uint32_t ve = W[h][2 * t], vo = W[h][2 * t + 1];
+                        ae[h][0] = (byte_and<0>(ve, TT::kMask) << TT::kShift) | rowbase;
+                        ae[h][1] = (byte_and<1>(ve, TT::kMask) << TT::kShift) | rowbase;
+                        ae[h][2] = (byte_and<2>(ve, TT::kMask) << TT::kShift) | rowbase;
+                        ae[h][3] = (byte_and<3>(ve, TT::kMask) << TT::kShift) | rowbase;
+                        ao[h][0] = (byte_and<0>(vo, TT::kMask) << TT::kShift) | rowbase;
+                        ao[h][1] = (byte_and<1>(vo, TT::kMask) << TT::kShift) | rowbase;
+                        ao[h][2] = (byte_and<2>(vo, TT::kMask) << TT::kShift) | rowbase;
+                        ao[h][3] = (byte_and<3>(vo, TT::kMask) << TT::kShift) | rowbase;
+                    }
+                    uint32_t we[2][4], wo[2][4];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            we[h][j] = *reinterpret_cast<const uint16_t *>(tt + ae[h][j]);
+                            wo[h][j] = *reinterpret_cast<const uint16_t *>(tt + ao[h][j]);
+                        }
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) P[h][j] = we[h][j] | (wo[h][j] << 16);
+                }
+                // second quad: the operand sits 8 lanes up in the same group of 16 (row_ror:8)
+                u32x4 X1;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) X1[d] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)X[t][d], 0x128, 0xf, 0xf, true);
+                const u32x4 a0 = {P[0][0], P[0][1], P[0][2], P[0][3]}, a1 = {P[1][0], P[1][1], P[1][2], P[1][3]};
+                acc[tile][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a0), __builtin_bit_cast(half8_t, X[t]),
+                                                                      acc[tile][0], 0, 0, 0);
+                acc[tile][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a1), __builtin_bit_cast(half8_t, X1),
+                                                                      acc[tile][1], 0, 0, 0);
+            }
+        }
+    };
+
+    const int nocts = chunks >> 3; // K % 256 == 0
+    const int npairs = (nocts + 1) >> 1;
+    const int p1 = (int)((long long)npairs * (wave + 1) / nwaves);
+    u32x4 XA[4], XB[4];
+    uint32_t QA[R][2][B], QB[R][2][B];
+    int p = (int)((long long)npairs * wave / nwaves); // < p1: the launcher starts no more waves than pairs
+    issue(2 * p, true, XA, QA);
+    for (; p < p1; ++p) {
+        const bool second = 2 * p + 1 < nocts;
+        issue(second ? 2 * p + 1 : 2 * p, second, XB, QB);
+        __builtin_amdgcn_sched_barrier(0); // keep the loads ahead of the arithmetic they overlap with
+        compute(XA, QA);
+        issue(p + 1 < p1 ? 2 * p + 2 : 2 * p, true, XA, QA);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(XB, QB);
+    }
+
+    // ---- acc[tile][r] of lane (i, kg): output row 4 kg + r of the tile, batch row i, over this wave's
+    //      columns; waves are added in fixed order
+    __syncthreads(); // every wave is done with the tables, whose memory now takes the partial sums
+#pragma unroll
+    for (int tile = 0; tile < R; ++tile)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[wave][tile][4 * kg + r][i] = acc[tile][0][r] + acc[tile][1][r];
+    __syncthreads();
+    for (int o = tid; o < R * kTileRows * 16; o += nth) {
+        const int n = o & 15, r = o >> 4; // r = row inside the workgroup's R tiles
+        float s = 0.f;
+        for (int w = 0; w < nwaves; ++w) s += red[w][r >> 4][r & 15][n];
+        const int row = row0 + r;
+        if (row < M && n < batch) {
+            const __half hv = __float2half_rn(s);
+            y[(size_t)n * M + row] = __builtin_bit_cast(uint16_t, hv);
+        }
+    }
+}
+
+template <int B, int R> static hipError_t launch_tile_r(const GemvArgs &a, hipStream_t stream)
+{
+    constexpr int kMaxWaves = 8;
+    const int npairs = (a.K / (8 * kChunkSlots) + 1) / 2;
+    // short rows: 4 waves, so that a wave still runs several passes of its loop
+    int nw = a.waves_per_group > 0 ? a.waves_per_group : a.K >= 12288 ? kMaxWaves : 4;
+    if (nw > npairs) nw = npairs;
+    const int tiles = (a.M + 15) / 16;
+    hipLaunchKernelGGL((gemv_tile_kernel<B, R, 64 * kMaxWaves>), dim3((tiles + R - 1) / R), dim3(64 * nw), 0, stream, a.slices,
+                       a.slice_bytes, a.lut, a.x, a.y, a.M, a.K, a.batch);
+    return hipGetLastError();
+}
+
+template <int B> static hipError_t launch_tile_b(const GemvArgs &a, hipStream_t stream)
+{
+    // two tiles per workgroup re-read and re-arrange the activations half as often, at more registers:
+    // measured faster on rows of 16384 columns or more only
+    const int r = a.variant == 9 ? 1 : a.variant == 10 ? 2 : a.K >= 16384 ? 2 : 1;
+    if (r == 2) return launch_tile_r<B, 2>(a, stream);
+    return launch_tile_r<B, 1>(a, stream);
+}
+
+// batch <= 8, K % 256 == 0 (the dispatcher checks)
+hipError_t launch_matrix_tile(const GemvArgs &a, hipStream_t stream)
+{
+    switch (a.b) {
+    case 3: return launch_tile_b<3>(a, stream);
+    case 4: return launch_tile_b<4>(a, stream);
+    case 5: return launch_tile_b<5>(a, stream);
+    case 6: return launch_tile_b<6>(a, stream);
+    case 7: return launch_tile_b<7>(a, stream);
+    case 8: return launch_tile_b<8>(a, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+} // namespace apgemv

@@ -21,7 +21,9 @@ struct GemvArgs {
     int variant;           // AP_VARIANT_*: 0 = choose; 1 = never the matrix-core kernel with in-wave exchange;
                            // 3 = that kernel whenever the shape allows it (batch >= 2, K % 128 == 0);
                            // 5 = the bank-per-lane kernel at batch 1, b >= 7;
-                           // 7 / 8 = two row groups per workgroup at batch 1 whenever possible / never
+                           // 7 / 8 = two row groups per workgroup at batch 1 whenever possible / never;
+                           // 9 / 10 = the 16-row-tile matrix-core kernel (batch >= 2, K % 256 == 0) with one /
+                           //          two tiles per workgroup
 };
 
 constexpr int kMaxMulti = 8;

@@ -108,17 +108,18 @@ def test_integer_table_pins_bit_order_end_to_end(B, b):
 
 
 # kernel families for the adversarial inputs: the dispatcher's own choice, the one-row-per-lane
-# matrix-core kernel for every b, the matrix-core kernel with in-wave exchange; the last two need
-# K % 128 == 0 and batch >= 3 / >= 2, which the shapes below satisfy
-FAMILIES = [dict(), dict(mfma_min_batch=-3), dict(variant=3)]
+# matrix-core kernel for every b, the matrix-core kernel with in-wave exchange, the matrix-core kernel
+# on tiles of 16 rows (one and two tiles per workgroup); the matrix-core kernels need K % 128 == 0
+# (K % 256 == 0 on tiles) and batch >= 3 / >= 2, which the shapes below satisfy
+FAMILIES = [dict(), dict(mfma_min_batch=-3), dict(variant=3), dict(variant=9), dict(variant=10)]
 
 
 @pytest.mark.parametrize("family", range(len(FAMILIES)))
 @pytest.mark.parametrize("batch", [1, 3, 5, 8])
 @pytest.mark.parametrize("b", ALL_BITS)
 def test_adversarial_tables(B, b, batch, family):
-    M, K = 48, 2048 + 128
-    assert K % 128 == 0                                   # so that the matrix-core kernels are reachable
+    M, K = 48, 2048 + 256
+    assert K % 256 == 0                                   # so that the matrix-core kernels are reachable
     idx, luts, x = inputs.make_case(16, M, K, batch=batch)
     rng = np.random.default_rng(b)
     E = 1 << b
@@ -145,8 +146,8 @@ def test_subnormal_centroids_are_not_flushed(B, b, batch, family):
     # every centroid is a binary16 subnormal (k * 2^-24), activations are large: a path that
     # flushed subnormal inputs to zero (the matrix instructions included) would return 0 where the
     # result is of order 10
-    M, K = 20, 2048 + 128
-    assert K % 128 == 0
+    M, K = 20, 2048 + 256
+    assert K % 256 == 0
     rng = np.random.default_rng(100 + b)
     idx = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
     lut = (rng.integers(1, 1024, size=(M, 1 << b)).astype(np.uint16)).view(np.float16)
@@ -196,6 +197,21 @@ def test_matrix_core_variant_with_in_block_exchange(B, batch):
         for (M, K) in [(37, 128), (70, 2048 + 640), (21, 3 * 2048 + 128), (9, 9 * 2048 + 256)]:
             idx, luts, x = inputs.make_case(21, M, K, batch=batch, sigma=0.01)
             pm = B.ap_pack(idx, luts).set_options(variant=B.VARIANT_EXCHANGE, row_groups=rg)
+            for b in ALL_BITS:
+                y = run_gemv(pm, b, x)
+                check_against_oracle(y, idx, luts[b], b, x)
+            pm.close()
+
+
+@pytest.mark.parametrize("batch", [2, 3, 4, 5, 6, 7, 8])
+def test_matrix_core_variant_on_tiles_of_16_rows(B, batch):
+    # forced for every b and batch >= 2: one octet of chunks, several spans with a ragged last span, an
+    # odd number of octets, more octet pairs than waves, rows not a multiple of 4 or 16 (tiles and row
+    # groups partly or wholly past the matrix), one and two tiles per workgroup
+    for variant in (B.VARIANT_TILE, B.VARIANT_TILE2):
+        for (M, K) in [(37, 256), (70, 2048 + 768), (21, 3 * 2048 + 256), (9, 9 * 2048 + 512), (130, 4096), (16, 512)]:
+            idx, luts, x = inputs.make_case(27, M, K, batch=batch, sigma=0.01)
+            pm = B.ap_pack(idx, luts).set_options(variant=variant)
             for b in ALL_BITS:
                 y = run_gemv(pm, b, x)
                 check_against_oracle(y, idx, luts[b], b, x)
@@ -402,7 +418,7 @@ def test_output_canaries_and_sparse_support(B):
 def test_option_values_are_checked(B, tiny):
     _, _, _, pm = tiny
     L = B.lib
-    for opt, bad in ((0, 9), (0, -1), (1, 0), (1, 5), (2, 10), (3, 2), (3, 6), (3, 9), (9, 0)):
+    for opt, bad in ((0, 9), (0, -1), (1, 0), (1, 5), (2, 10), (3, 2), (3, 6), (3, 11), (9, 0)):
         assert L.ap_set_option(pm.handle, opt, bad) == 1, (opt, bad)
     for opt, good, default in ((0, 2, 0), (1, 1, -1), (2, 9, 0), (3, 1, 0)):
         assert L.ap_set_option(pm.handle, opt, good) == 0
