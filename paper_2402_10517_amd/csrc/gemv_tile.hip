@@ -60,6 +60,7 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 5))) vo
     constexpr int kTabBytes = R * TT::kTileBytes, kRedBytes = (MAXT / 64) * R * kTileRows * 16 * 4;
     __shared__ __attribute__((aligned(16))) uint8_t smem[kTabBytes > kRedBytes ? kTabBytes : kRedBytes];
     uint8_t *tab = smem;
+    __shared__ __attribute__((aligned(16))) uint16_t nat[TT::kPair ? R * kTileRows * 8 : 8]; // natural rows (3-bit path)
     float(*red)[R][kTileRows][16] = reinterpret_cast<float(*)[R][kTileRows][16]>(smem);
 
     const int tid = threadIdx.x, nth = blockDim.x;
@@ -73,27 +74,6 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 5))) vo
     const int row0 = g0 * kRowsPerGroup;
     const int chunks = K / kChunkSlots;
     const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
-
-    // ---- tables of the R tiles into LDS (rows past the matrix repeat the last row; never stored).
-    // Thread e writes copy (e / 16) % 2 of row e % 16: the 32 lanes of an LDS clock hit 32 different banks
-    // (with one row per wave every lane of a store would land in the same bank).
-    {
-        const int srow = tid & 15, scopy = (tid >> 4) & 1;
-        constexpr int kPerRow = TT::kPair ? 64 : (1 << B) / 2; // pair entries, or dwords of two entries
-        for (int e = tid >> 5; e < R * kPerRow; e += nth >> 5) {
-            const int tile = e / kPerRow, d = e % kPerRow;
-            const int row = row0 + tile * kTileRows + srow < M ? row0 + tile * kTileRows + srow : M - 1;
-            uint8_t *base = tab + tile * TT::kTileBytes + ((srow << 2) | (scopy << 6));
-            if constexpr (TT::kPair) {
-                *reinterpret_cast<uint32_t *>(base + (TT::byte_of(d) << TT::kShift)) = pair_entry(lut + (size_t)row * 8, d);
-            } else {
-                const uint32_t v = reinterpret_cast<const uint32_t *>(lut + ((size_t)row << B))[d];
-                *reinterpret_cast<uint16_t *>(base + (TT::byte_of(2 * d) << TT::kShift)) = (uint16_t)v;
-                *reinterpret_cast<uint16_t *>(base + (TT::byte_of(2 * d + 1) << TT::kShift)) = (uint16_t)(v >> 16);
-            }
-        }
-    }
-    __syncthreads();
 
     // ---- per-lane offsets of the slice loads: lane 32 p + 4 c + r loads row r of row group 2 half + p of
     // the tile, chunk c of the octet
@@ -236,7 +216,71 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 5))) vo
     u32x4 XA[4], XB[4];
     uint32_t QA[R][2][B], QB[R][2][B];
     int p = (int)((long long)npairs * wave / nwaves); // < p1: the launcher starts no more waves than pairs
-    issue(2 * p, true, XA, QA);
+    // ---- tables of the R tiles into LDS (rows past the matrix repeat the last row; never stored).
+    // Thread (row = tid % 16, copy = (tid / 16) % 2, part = tid / 32) writes the entries of the pieces
+    // part, part + nparts, ... of its row and copy: the 32 lanes of an LDS clock hit 32 different banks
+    // (with one row per wave every lane of a store would land in the same bank).  A thread loads 16
+    // bytes at a time and issues its loads before the first store that depends on them (one dword load
+    // per loop pass cost a memory round trip per pass and one cache access per lane: 4 to 7 us per
+    // workgroup).  The loads of the wave's first octet go out between the table loads and the table
+    // stores, so that they are in flight during the stores and do not delay the tables (loads return in
+    // order).
+    {
+        const int srow = tid & 15, scopy = (tid >> 4) & 1, part = tid >> 5, nparts = nth >> 5;
+        if constexpr (TT::kPair) {
+            // natural rows (8 entries = 16 bytes each) first, then the pair entries from LDS
+            for (int e = tid; e < R * kTileRows * 4; e += nth) {
+                const int r = e >> 2;
+                const int row = row0 + r < M ? row0 + r : M - 1;
+                reinterpret_cast<uint32_t *>(nat)[e] = reinterpret_cast<const uint32_t *>(lut + (size_t)row * 8)[e & 3];
+            }
+            issue(2 * p, true, XA, QA);
+            __syncthreads();
+#pragma unroll
+            for (int tile = 0; tile < R; ++tile) {
+                uint8_t *base = tab + tile * TT::kTileBytes + ((srow << 2) | (scopy << 6));
+                for (int d = part; d < 64; d += nparts)
+                    *reinterpret_cast<uint32_t *>(base + (TT::byte_of(d) << TT::kShift)) = pair_entry(nat + (tile * kTileRows + srow) * 8, d);
+            }
+        } else {
+            constexpr int kPieces = (2 << B) / 16; // 16-byte pieces (8 entries) of a row's table
+            constexpr int kBurst = 4;              // pieces per thread in the first pass: all of them from 4 waves on
+            auto store_piece = [&](uint8_t *base, int pc, const u32x4 &v) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    *reinterpret_cast<uint16_t *>(base + (TT::byte_of(8 * pc + 2 * e) << TT::kShift)) = (uint16_t)v[e];
+                    *reinterpret_cast<uint16_t *>(base + (TT::byte_of(8 * pc + 2 * e + 1) << TT::kShift)) = (uint16_t)(v[e] >> 16);
+                }
+            };
+            const u32x4 *src[R];
+            uint8_t *base[R];
+            u32x4 v[R][kBurst];
+#pragma unroll
+            for (int tile = 0; tile < R; ++tile) {
+                const int row = row0 + tile * kTileRows + srow < M ? row0 + tile * kTileRows + srow : M - 1;
+                src[tile] = reinterpret_cast<const u32x4 *>(lut + ((size_t)row << B));
+                base[tile] = tab + tile * TT::kTileBytes + ((srow << 2) | (scopy << 6));
+#pragma unroll
+                for (int j = 0; j < kBurst; ++j) {
+                    const int pc = part + j * nparts;
+                    v[tile][j] = src[tile][pc < kPieces ? pc : kPieces - 1];
+                }
+            }
+            issue(2 * p, true, XA, QA);
+#pragma unroll
+            for (int tile = 0; tile < R; ++tile) {
+#pragma unroll
+                for (int j = 0; j < kBurst; ++j) {
+                    const int pc = part + j * nparts;
+                    if (pc < kPieces) store_piece(base[tile], pc, v[tile][j]);
+                }
+                // workgroups of fewer than 4 waves (rows of less than 2048 columns) at b >= 7: the rest
+                for (int pc = part + kBurst * nparts; pc < kPieces; pc += nparts) store_piece(base[tile], pc, src[tile][pc]);
+            }
+        }
+    }
+    __syncthreads();
+
     for (; p < p1; ++p) {
         const bool second = 2 * p + 1 < nocts;
         issue(second ? 2 * p + 1 : 2 * p, second, XB, QB);
