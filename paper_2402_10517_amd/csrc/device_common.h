@@ -241,7 +241,9 @@ __device__ constexpr int slice_with_rot(int B, int p)
 // classes u mod 2 (the two sources occupy alternating bits), level 2 joins {4c..4c+3} for u mod 4,
 // level 3 joins all eight for each u.  8 slices cost 8 + 8 + 8 selects and 7 rotates per 32 weights
 // instead of 8 x 7 selects; absent rotations (B < 8) drop their selects.
-template <int B>
+// EXTRA more bits of right rotation: byte j of W[u] is then the index byte shifted right by EXTRA, with the
+// low bits of byte j + 1 above it (for callers that mask the bytes afterwards).
+template <int B, int EXTRA = 0>
 __device__ __forceinline__ void merge_words(const uint32_t (&q)[B], uint32_t (&W)[8])
 {
     constexpr bool kPair = Table<B>::kPair;
@@ -278,7 +280,7 @@ __device__ __forceinline__ void merge_words(const uint32_t (&q)[B], uint32_t (&W
         uint32_t v;
         if (has2[0] && has2[1]) v = bitsel(rotl_c(0x0F0F0F0Fu, u), lo, hi);
         else v = has2[0] ? lo : hi;
-        W[u] = rotr_v(v, u);
+        W[u] = rotr_v(v, u + EXTRA);
     }
 }
 template <int B>

@@ -13,17 +13,19 @@ hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream)
     // and 8 copies of every table; measured slower than the shared-table kernel on every Llama shape
     // (b = 8: 8.2 / 17.7 / 19.6 us against 6.8 / 12.0 / 12.7 us on the 7B shapes), so only on request.
     if (a.batch == 1 && B >= 7 && a.variant == 5) return launch_quad(a, stream);
-    // The matrix-core kernel on tiles of 16 rows (K % 256 == 0).  Measured on the 13B and 70B shapes at
+    // The matrix-core kernel on tiles of 16 rows (K % 256 == 0).  Measured on the 7B, 13B and 70B shapes at
     // batch 2, 3, 4, 6, 8 against the kernels below: at batch >= 5 it wins on every matrix with at least
-    // 1024 groups of rows (5 to 49 %, most at small b and long rows; level at b = 8 on the 13B shapes);
-    // at batch 3 and 4 it wins by 5 to 30 % on rows of 16384 columns or more and is level elsewhere; at
-    // batch 2, and on 1024 x 8192 at every batch, the ALU kernels are faster.
+    // 1024 groups of rows (5 to 60 %, most at small b and long rows); at batch 3 and 4 it wins by 5 to
+    // 40 % on matrices with at least 2048 groups of rows and on rows of 16384 columns or more (level at
+    // b = 5, 6 on 28672 x 8192) and loses on smaller ones; at batch 2, and on 1024 x 8192 at every
+    // batch, the ALU kernels are faster.
     // variant: 9 / 10 = this kernel with one / two tiles per workgroup whenever the shape allows; any
     // other tuning override keeps the call away from it.
     if (a.batch >= 2 && a.K % 256 == 0) {
         const int groups = padded_rows(a.M) / kRowsPerGroup;
         const bool tuned = a.row_groups_per_wg >= 0 || a.mfma_min_batch != 0 || a.waves_per_group != 0;
-        const bool pays = a.variant == 0 && !tuned && groups >= 1024 && (a.batch >= 5 || (a.batch >= 3 && a.K >= 16384));
+        const bool pays = a.variant == 0 && !tuned && groups >= 1024 &&
+                          (a.batch >= 5 || (a.batch >= 3 && (a.K >= 16384 || groups >= 2048)));
         if (a.variant == 9 || a.variant == 10 || pays) return launch_matrix_tile(a, stream);
     }
     // What is left for batch >= 2 (K not a multiple of 256, smaller matrices, batch 2..4) was settled by

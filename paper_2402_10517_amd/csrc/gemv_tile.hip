@@ -17,19 +17,23 @@
 //   * The activations of a run of an octet are 128 contiguous bytes per batch row: lane 8 n + p loads
 //     the 16 bytes of batch row n for chunk p, so one instruction covers 8 batch rows line by line (a
 //     lane-per-row order costs one cache access per lane).  Four ds_bpermute per run move them to the
-//     lanes of the matrix instruction: lane (i, kg) takes batch row i % 8, chunk 4 (i / 8) + kg; lanes
-//     i < 8 then hold the first quad's operand, and a rotation by 8 lanes inside each group of 16
-//     brings them the second quad's.  Output columns i >= 8 are never stored, so what the matrix
-//     instruction gets there does not matter; batch rows that do not exist read zeros (their buffer
-//     offset is out of range: no memory traffic).
+//     lanes of the matrix instruction: lane (i, kg) takes batch row i % 8, chunk 4 (i / 8) + kg.  Both
+//     quads of the octet use that register as B: output columns 0..7 of the first quad's instruction
+//     and columns 8..15 of the second's are the products wanted (batch rows 0..7 each), the other
+//     halves multiply one quad's weights with the other quad's activations and are dropped, so each
+//     quad has its own accumulator and the final sum takes column n of one and n + 8 of the other.
+//     Batch rows that do not exist read zeros (their buffer offset is out of range: no memory traffic).
 //   * One instruction takes one run of 8 consecutive columns: their indices are the bytes of the
 //     merged words of the run's even and odd slots, the activations the lane's 16 bytes of that run.
 //   * The LDS serves 32 lanes per clock, here 16 rows x 2 lane groups, so every (row, lane group
-//     parity) gets a bank of its own: each row's table is stored twice, entry v (the masked index
-//     byte) of row i for lane groups of parity c is the low half of the dword at
-//     (v << s) | (c << 6) | (i << 2), with s such that the lowest index bit lands on address bit 7;
-//     no two lanes of a clock share a bank.  The 3-bit path keeps its 64-entry table of centroid
-//     pairs, one pair per dword.
+//     parity) gets a bank of its own: each row's table is stored twice, entry v of row i for lane
+//     groups of parity c is the low half of the dword at (v << s) | (c << 6) | (i << 2); no two lanes
+//     of a clock share a bank.  For b <= 7, s = 8 and v = the index byte shifted down to its lowest
+//     used bit (the index words are rotated that much further and masked, once per 4 lookups), so
+//     that one v_perm_b32 per lookup builds the address from the word's byte and the lane's base; for
+//     b = 8 that would need 64 KB per tile, so s = 7 and the address takes two operations (a byte
+//     select and a shift-or).  The 3-bit path keeps its 64-entry table of centroid pairs, one pair
+//     per dword.
 // Requires K % 256 == 0 (an octet is entirely inside or outside a ragged last span) and batch <= 8.
 #include "device_common.h"
 #include "launchers.h"
@@ -40,12 +44,21 @@ template <int B> struct TileTable {
     static constexpr bool kPair = (B == 3);
     static constexpr uint32_t kMask = kPair ? 0xFCu : Table<B>::addr_mask(); // index bits inside a merged byte
     static constexpr int kLow = (kMask & 1) ? 0 : (kMask & 2) ? 1 : 2;       // lowest of them
-    static constexpr int kShift = 7 - kLow;
-    static constexpr int kTileBytes = (int)((kMask >> kLow) + 1) << 7; // 16 rows x 2 copies x 4 bytes per entry
-    // masked byte value of the entry stored at position p of a row (lut_stored_pos order; pair index for B = 3)
+    static constexpr bool kPerm = (B <= 7);                                  // address by one v_perm_b32
+    static constexpr int kExtra = kPerm ? kLow : 0;                          // extra rotation of the index words
+    static constexpr uint32_t kClean = (kMask >> kExtra) * 0x01010101u;      // index bits of the rotated words
+    static constexpr int kShift = kPerm ? 8 : 7 - kLow;                      // entry value -> address
+    static constexpr int kTileBytes = (int)((kMask >> kLow) + 1) << (kPerm ? 8 : 7); // 16 rows x 2 copies x 4 bytes per entry (x 2 unused)
+    // value in a (rotated) index byte of the entry stored at position p of a row (lut_stored_pos order; pair index for B = 3)
     __device__ static constexpr uint32_t byte_of(uint32_t p)
     {
-        return kPair ? p << 2 : B == 4 ? (((p & 8u) << 3) | ((p & 7u) << 2)) : p << kLow;
+        return (kPair ? p << 2 : B == 4 ? (((p & 8u) << 3) | ((p & 7u) << 2)) : p << kLow) >> kExtra;
+    }
+    // LDS address of the entry selected by byte J of the index word w, for a lane with base `rowbase` (< 128)
+    template <int J> __device__ static __forceinline__ uint32_t addr(uint32_t w, uint32_t rowbase)
+    {
+        if constexpr (kPerm) return __builtin_amdgcn_perm(rowbase, w, 0x0c0c0004u | ((uint32_t)J << 8));
+        else return (byte_and<J>(w, kMask) << kShift) | rowbase;
     }
 };
 
@@ -150,8 +163,14 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 5))) vo
                     q[0][s] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm_src, (int)sw[0]);
                     q[1][s] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm_src, (int)sw[1]);
                 }
-                merge_words<B>(q[0], W[0]);
-                merge_words<B>(q[1], W[1]);
+                merge_words<B, TT::kExtra>(q[0], W[0]);
+                merge_words<B, TT::kExtra>(q[1], W[1]);
+                if constexpr (TT::kPerm) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int u = 0; u < 8; u += TT::kPair ? 2 : 1) W[h][u] &= TT::kClean;
+                }
             }
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
@@ -161,10 +180,10 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 5))) vo
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         const uint32_t v = W[h][2 * t];
-                        ad[h][0] = (byte_and<0>(v, TT::kMask) << TT::kShift) | rowbase;
-                        ad[h][1] = (byte_and<1>(v, TT::kMask) << TT::kShift) | rowbase;
-                        ad[h][2] = (byte_and<2>(v, TT::kMask) << TT::kShift) | rowbase;
-                        ad[h][3] = (byte_and<3>(v, TT::kMask) << TT::kShift) | rowbase;
+                        ad[h][0] = TT::template addr<0>(v, rowbase);
+                        ad[h][1] = TT::template addr<1>(v, rowbase);
+                        ad[h][2] = TT::template addr<2>(v, rowbase);
+                        ad[h][3] = TT::template addr<3>(v, rowbase);
                     }
 #pragma unroll
                     for (int h = 0; h < 2; ++h)
@@ -175,14 +194,14 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 5))) vo
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         const uint32_t ve = W[h][2 * t], vo = W[h][2 * t + 1];
-                        ae[h][0] = (byte_and<0>(ve, TT::kMask) << TT::kShift) | rowbase;
-                        ae[h][1] = (byte_and<1>(ve, TT::kMask) << TT::kShift) | rowbase;
-                        ae[h][2] = (byte_and<2>(ve, TT::kMask) << TT::kShift) | rowbase;
-                        ae[h][3] = (byte_and<3>(ve, TT::kMask) << TT::kShift) | rowbase;
-                        ao[h][0] = (byte_and<0>(vo, TT::kMask) << TT::kShift) | rowbase;
-                        ao[h][1] = (byte_and<1>(vo, TT::kMask) << TT::kShift) | rowbase;
-                        ao[h][2] = (byte_and<2>(vo, TT::kMask) << TT::kShift) | rowbase;
-                        ao[h][3] = (byte_and<3>(vo, TT::kMask) << TT::kShift) | rowbase;
+                        ae[h][0] = TT::template addr<0>(ve, rowbase);
+                        ae[h][1] = TT::template addr<1>(ve, rowbase);
+                        ae[h][2] = TT::template addr<2>(ve, rowbase);
+                        ae[h][3] = TT::template addr<3>(ve, rowbase);
+                        ao[h][0] = TT::template addr<0>(vo, rowbase);
+                        ao[h][1] = TT::template addr<1>(vo, rowbase);
+                        ao[h][2] = TT::template addr<2>(vo, rowbase);
+                        ao[h][3] = TT::template addr<3>(vo, rowbase);
                     }
                     uint32_t we[2][4], wo[2][4];
 #pragma unroll
@@ -197,14 +216,11 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 5))) vo
 #pragma unroll
                         for (int j = 0; j < 4; ++j) P[h][j] = we[h][j] | (wo[h][j] << 16);
                 }
-                // second quad: the operand sits 8 lanes up in the same group of 16 (row_ror:8)
-                u32x4 X1;
-#pragma unroll
-                for (int d = 0; d < 4; ++d) X1[d] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)X[t][d], 0x128, 0xf, 0xf, true);
+                // both quads against the same B: columns 0..7 of the first product and 8..15 of the second count
                 const u32x4 a0 = {P[0][0], P[0][1], P[0][2], P[0][3]}, a1 = {P[1][0], P[1][1], P[1][2], P[1][3]};
                 acc[tile][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a0), __builtin_bit_cast(half8_t, X[t]),
                                                                       acc[tile][0], 0, 0, 0);
-                acc[tile][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a1), __builtin_bit_cast(half8_t, X1),
+                acc[tile][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a1), __builtin_bit_cast(half8_t, X[t]),
                                                                       acc[tile][1], 0, 0, 0);
             }
         }
@@ -291,18 +307,19 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 5))) vo
         compute(XB, QB);
     }
 
-    // ---- acc[tile][r] of lane (i, kg): output row 4 kg + r of the tile, batch row i, over this wave's
-    //      columns; waves are added in fixed order
+    // ---- acc[tile][h][r] of lane (i, kg): output row 4 kg + r of the tile over the wave's columns of quad
+    //      h; column i of the h = 0 accumulator is batch row i for i < 8, column i of the h = 1 accumulator
+    //      is batch row i - 8 for i >= 8.  Waves are added in fixed order
     __syncthreads(); // every wave is done with the tables, whose memory now takes the partial sums
 #pragma unroll
     for (int tile = 0; tile < R; ++tile)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) red[wave][tile][4 * kg + r][i] = acc[tile][0][r] + acc[tile][1][r];
+        for (int r = 0; r < 4; ++r) red[wave][tile][4 * kg + r][i] = i < 8 ? acc[tile][0][r] : acc[tile][1][r];
     __syncthreads();
-    for (int o = tid; o < R * kTileRows * 16; o += nth) {
-        const int n = o & 15, r = o >> 4; // r = row inside the workgroup's R tiles
+    for (int o = tid; o < R * kTileRows * 8; o += nth) {
+        const int n = o & 7, r = o >> 3; // r = row inside the workgroup's R tiles
         float s = 0.f;
-        for (int w = 0; w < nwaves; ++w) s += red[w][r >> 4][r & 15][n];
+        for (int w = 0; w < nwaves; ++w) s += red[w][r >> 4][r & 15][n] + red[w][r >> 4][r & 15][n + 8];
         const int row = row0 + r;
         if (row < M && n < batch) {
             const __half hv = __float2half_rn(s);
