@@ -36,6 +36,21 @@ def test_config3_llama13b_shapes_every_row(B, M, K):
     pm.close()
 
 
+@pytest.mark.parametrize("M,K", inputs.CONFIGS[2]["shapes"] + inputs.CONFIGS[3]["shapes"])
+def test_config2_and_3_shapes_sampled_rows_at_batch_3_to_8(B, M, K):
+    # the dispatcher's own choice at small batches: the tile kernel on the taller matrices, the ALU
+    # kernels on the others
+    idx, luts, x = inputs.make_case(3, M, K, batch=8)
+    pm = B.ap_pack(idx, luts)
+    rows = np.unique(np.concatenate([np.arange(0, 20), np.arange(M - 20, M),
+                                     np.random.default_rng(M + K).integers(0, M, size=256)]))
+    for b in ALL_BITS:
+        for batch in (3, 4, 5, 8):
+            y = run_gemv(pm, b, x[:batch])
+            check_against_oracle(y, idx, luts[b], b, x[:batch], rows=rows)
+    pm.close()
+
+
 @pytest.mark.parametrize("M,K", inputs.CONFIGS[5]["shapes"])
 def test_config5_llama70b_shapes_every_row_at_batch_1_sampled_rows_at_batch_2_to_8(B, M, K):
     idx, luts, x = inputs.make_case(5, M, K, batch=8, sigma=0.01)
