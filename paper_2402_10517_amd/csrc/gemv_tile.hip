@@ -63,7 +63,7 @@ template <int B> struct TileTable {
 };
 
 template <int B, int R, int MAXT>
-__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 5))) void gemv_tile_kernel(
+__global__ __launch_bounds__(MAXT) void gemv_tile_kernel(
     const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
     const uint16_t *__restrict__ x, uint16_t *__restrict__ y, int M, int K, int batch)
 {
