@@ -33,14 +33,15 @@ typedef enum {
     AP_ERR_BITS = 3,             /* n outside 3..8, b outside 3..n, or no table given for b */
     AP_ERR_INDEX_RANGE = 4,      /* an index >= 2^n */
     AP_ERR_BUFFER_TOO_SMALL = 5, /* destination smaller than ap_packed_size */
-    AP_ERR_BATCH = 6,            /* batch outside 1..8 */
+    AP_ERR_BATCH = 6,            /* batch outside 1..16 (ap_gemv) or 1..8 (ap_gemv_multi) */
     AP_ERR_HIP = 7,              /* a HIP runtime call or kernel launch failed */
     AP_ERR_NO_MEMORY = 8         /* host memory (a handle, the pinned staging buffer) could not be allocated */
 } ap_status;
 
 #define AP_MIN_BITS 3
 #define AP_MAX_BITS 8
-#define AP_MAX_BATCH 8
+#define AP_MAX_BATCH 16      /* ap_gemv */
+#define AP_MAX_MULTI_BATCH 8 /* ap_gemv_multi */
 #define AP_BLOB_ALIGN 256
 
 /*
@@ -107,7 +108,9 @@ ap_status ap_unpack(const ap_matrix *h, uint8_t *idx_host_out, void *stream);
  *   h      packed matrix; b: 3 <= b <= n and a table for b was packed (else AP_ERR_BITS)
  *   x_dev  device, batch*K binary16 row-major, 16-byte aligned
  *   y_dev  device, batch*M binary16 row-major, 2-byte aligned; must not overlap x_dev or the blob
- *   batch  1..8 (the paper switches to a dequantise + dense GEMM path above that, Section 6.2)
+ *   batch  1..16 (the paper switches to a dequantise + dense GEMM path above about 16, Section 6.2).
+ *          The kernels take up to 8 activation rows; batches 9..16 run as two passes on the stream, the
+ *          first over rows 0..7, and cost what the two batches cost separately
  * Products are exact in binary32, accumulation is binary32, the result is rounded to binary16
  * (round to nearest even).  Asynchronous on `stream`; allocates nothing, synchronises nothing,
  * never repacks; the bit-width is chosen per call.  Results are deterministic (no atomics).

@@ -187,7 +187,14 @@ extern "C" ap_status ap_gemv(const ap_matrix *h, int b, const void *x_dev, void 
     a.row_groups_per_wg = h->row_groups_per_wg;
     a.mfma_min_batch = h->mfma_min_batch;
     a.variant = h->variant;
-    return launch_gemv(a, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
+    // the kernels take up to 8 activation rows: larger batches in passes of 8 rows
+    for (int first = 0; first < batch; first += AP_MAX_MULTI_BATCH) {
+        a.x = static_cast<const uint16_t *>(x_dev) + (size_t)first * a.K;
+        a.y = static_cast<uint16_t *>(y_dev) + (size_t)first * a.M;
+        a.batch = batch - first < AP_MAX_MULTI_BATCH ? batch - first : AP_MAX_MULTI_BATCH;
+        if (launch_gemv(a, static_cast<hipStream_t>(stream)) != hipSuccess) return AP_ERR_HIP;
+    }
+    return AP_OK;
 }
 
 static ap_status fill_args(const ap_matrix *h, int b, GemvArgs *a)
@@ -253,7 +260,7 @@ extern "C" ap_status ap_gemv_list(const ap_gemv_list_item *items, int count, voi
 extern "C" ap_status ap_gemv_multi(const ap_gemv_item *items, int count, int b, int batch, void *stream)
 {
     if (!items || count < 1 || count > kMaxMulti) return AP_ERR_INVALID_ARG;
-    if (batch < 1 || batch > AP_MAX_BATCH) return AP_ERR_BATCH;
+    if (batch < 1 || batch > AP_MAX_MULTI_BATCH) return AP_ERR_BATCH;
     if (batch == 1) { // any shapes: the list kernel, every item at bit-width b
         ListArgs la;
         std::memset(&la, 0, sizeof(la));

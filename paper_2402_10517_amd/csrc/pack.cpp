@@ -283,7 +283,7 @@ extern "C" const char *ap_strerror(ap_status s)
     case AP_ERR_BITS: return "bit-width not supported for this matrix";
     case AP_ERR_INDEX_RANGE: return "index value does not fit the parent bit-width";
     case AP_ERR_BUFFER_TOO_SMALL: return "buffer smaller than ap_packed_size";
-    case AP_ERR_BATCH: return "batch outside 1..8";
+    case AP_ERR_BATCH: return "batch outside the supported range";
     case AP_ERR_HIP: return "HIP runtime call or kernel launch failed";
     case AP_ERR_NO_MEMORY: return "host memory could not be allocated";
     }

@@ -72,6 +72,31 @@ def test_batches_one_to_eight(B, batch, b):
     pm.close()
 
 
+@pytest.mark.parametrize("batch", [9, 12, 16])
+def test_batches_nine_to_sixteen_run_as_two_passes(B, batch):
+    # rows 8.. of a larger batch equal a separate call on those rows, bit for bit; canaries around y;
+    # shapes that reach the ALU kernels and (K % 256 == 0, forced) the tile kernel in both passes
+    import ctypes
+    import torch
+    for (M, K, opts) in [(132, 2048 + 96, {}), (70, 2048 + 768, dict(variant=9))]:
+        idx, luts, x = inputs.make_case(29, M, K, batch=batch, sigma=0.01)
+        pm = B.ap_pack(idx, luts).set_options(**opts)
+        guard = 64
+        sp = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        xd = torch.from_numpy(x).cuda()
+        for b in (3, 5, 8):
+            ybuf = torch.full((guard + batch * M + guard,), -7.0, dtype=torch.float16, device="cuda")
+            assert B.lib.ap_gemv(pm.handle, b, xd.data_ptr(), ybuf.data_ptr() + 2 * guard, batch, sp) == 0
+            torch.cuda.synchronize()
+            out = ybuf.cpu().numpy()
+            assert np.all(out[:guard] == -7.0) and np.all(out[-guard:] == -7.0)
+            y = out[guard:-guard].reshape(batch, M)
+            check_against_oracle(y, idx, luts[b], b, x)
+            y_tail = run_gemv(pm, b, x[8:])
+            assert np.array_equal(y[8:].view(np.uint16), y_tail.view(np.uint16))
+        pm.close()
+
+
 @pytest.mark.parametrize("b", ALL_BITS)
 def test_one_hot_activation_is_exact(B, b):
     M, K = 64, 2048 + 96
@@ -410,7 +435,7 @@ def test_output_canaries_and_sparse_support(B):
     for b in (5, 6, 7, 2, 9):
         assert B.lib.ap_gemv(pm.handle, b, xd.data_ptr(), ybuf.data_ptr(), 3, sp) == 3
     assert B.lib.ap_gemv(pm.handle, 3, xd.data_ptr(), ybuf.data_ptr(), 0, sp) == 6
-    assert B.lib.ap_gemv(pm.handle, 3, xd.data_ptr(), ybuf.data_ptr(), 9, sp) == 6
+    assert B.lib.ap_gemv(pm.handle, 3, xd.data_ptr(), ybuf.data_ptr(), 17, sp) == 6
     assert B.lib.ap_gemv(pm.handle, 3, xd.data_ptr() + 2, ybuf.data_ptr(), 1, sp) == 1
     pm.close()
 
