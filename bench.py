@@ -192,7 +192,8 @@ def decode_step_rows(np, torch, B, inputs, dev, modes, replays):
     return results, seq
 
 
-def per_call_rows(torch, B, inputs, dev, config, batches, bits, sp, variant=0, detail=False, waves=0, mfma_min_batch=0):
+def per_call_rows(torch, B, inputs, dev, config, batches, bits, sp, variant=0, detail=False, waves=0, mfma_min_batch=0,
+                  warm=False):
     """Single ap_gemv calls of every shape of `config`: back-to-back launches over rotating device
     copies between two events (median of 3 runs); the average includes the dispatch gap between
     dependent launches, so it is at least the kernel's own duration."""
@@ -228,6 +229,8 @@ def per_call_rows(torch, B, inputs, dev, config, batches, bits, sp, variant=0, d
                 nbytes = inputs.algorithmic_bytes(M, K, b, batch)
                 rows.append(dict(config=config, M=M, K=K, b=b, batch=batch, us=round(us, 3), bytes=nbytes,
                                  GBps=round(nbytes / us / 1e3, 1), frac_of_peak=round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)))
+                if warm:   # the same device copy every call: the matrix stays in the 256 MB last-level cache
+                    rows[-1]["us_cache_warm"] = round(timed_launches(torch, lambda r: call(0), reps), 3)
                 if detail:
                     print("  %5dx%-5d b=%d batch %d  %8.2f us  %7.1f GB/s  %5.1f%% of 8 TB/s" %
                           (M, K, b, batch, us, nbytes / us / 1e3, 100 * nbytes / us / 1e3 / HBM_PEAK_GBPS), file=sys.stderr)
@@ -440,7 +443,7 @@ def main():
     list_launches = len({min(8, (cs["K"] + 2047) // 2048) for cs in cases})
     list_call = dict(products=len(bits) * len(cases), launches=list_launches, us=round(list_us, 3), bytes=step_bytes,
                      GBps=round(step_bytes / list_us / 1e3, 1), frac_of_peak=round(step_bytes / list_us / 1e3 / HBM_PEAK_GBPS, 4))
-    per_call = per_call_rows(torch, B, inputs, dev, 2, [1], bits, sp, args.variant, args.detail)
+    per_call = per_call_rows(torch, B, inputs, dev, 2, [1], bits, sp, args.variant, args.detail, warm=True)
     # counter calibration launches (outside every timed region): a plain read of known size with the slice
     # loads' access shape, so that a rocprofv3 --pmc run of this script holds its own reference (for
     # writes: the device-to-device copies of the packed matrices made above)
@@ -450,6 +453,22 @@ def main():
             raise RuntimeError("ap_probe_read failed")
     torch.cuda.synchronize()
     del probe
+    # streaming-read ceiling: the same plain read kernel over 240 MB pieces of a 960 MB buffer in rotation
+    # (HBM-cold like the products), back-to-back launches between two events
+    big = torch.empty(960 << 20, dtype=torch.uint8, device=dev)
+    piece = 240 << 20
+
+    def read_piece(r):
+        if B.lib.ap_probe_read(big.data_ptr() + (r % 4) * piece, piece, sp) != 0:
+            raise RuntimeError("ap_probe_read failed")
+    for r in range(4):
+        read_piece(r)
+    torch.cuda.synchronize()
+    read_us = timed_launches(torch, read_piece, 20)
+    read_ceiling = dict(bytes=piece, us=round(read_us, 2), GBps=round(piece / read_us / 1e3, 1),
+                        frac_of_peak=round(piece / read_us / 1e3 / HBM_PEAK_GBPS, 4))
+    del big
+    torch.cuda.empty_cache()
     if args.issue == "list":
         kernel = "gemv_list_kernel<0,512>"   # template argument 0 = list of mixed bit-widths
         dom_bytes, dom_us = step_bytes // list_launches, list_us / list_launches
@@ -466,7 +485,8 @@ def main():
     traffic, traffic_commit = measured_traffic(kernel) if args.weights == "uniform" and not args.variant else (None, None)
     achieved = dom_bytes / dom_us / 1e3
     roofline = dict(bound="hbm", kernel=kernel, achieved=round(achieved, 1), peak=HBM_PEAK_GBPS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBPS, 4), bytes_per_launch=dom_bytes,
+                    frac=round(achieved / HBM_PEAK_GBPS, 4), frac_of_read_ceiling=round(achieved / read_ceiling["GBps"], 4),
+                    bytes_per_launch=dom_bytes,
                     avg_launch_us=round(dom_us, 3), traffic=traffic, traffic_from="profiles/gemv_config2_hbm_traffic.txt"
                     + (" @ " + traffic_commit if traffic_commit else ""))
 
@@ -548,7 +568,7 @@ def main():
                            device_copies=COPIES, launch="hip-graph" if not args.no_graph else "python-loop"),
                frac_of_hbm_peak=round(value / HBM_PEAK_GBPS, 4), us_per_product=round(ms_per_step * 1e3 / (len(bits) * len(cases)), 3),
                wall_ms=round(wall_ms, 2), roofline=roofline, cpu_baseline=cpu, other_issue=other_row,
-               list_call=list_call, per_call=per_call, **extra)
+               list_call=list_call, read_ceiling=read_ceiling, per_call=per_call, **extra)
     print(json.dumps(out))
 
 
