@@ -1,6 +1,6 @@
 """GPU test of the entry point that allocates nothing (ap_gemm_static) against ap_gemm.
 
-Collected last (file name): the full test run uses -x, and a failure here must not hide other tests.
+Collected last (file name): a run with -x stops at the first failure, and a failure here must not hide other tests.
 """
 import ctypes
 
