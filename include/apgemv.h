@@ -167,7 +167,11 @@ ap_status ap_set_option(ap_matrix *h, int option, int value);
  * any shapes go together; x_dev/y_dev may be shared or distinct per item (outputs must not overlap).
  * At batch 1 and 2 each output is bit-identical to the one ap_gemv produces with default options (same
  * kernel per row group); at larger batches ap_gemv may pick another variant with a different
- * summation order, and both meet the same tolerance.  Same argument rules and error codes as ap_gemv.
+ * summation order, and both meet the same tolerance.  The kernel is chosen from the launch as a whole
+ * (b, batch, K, the sum of the rows); of the per-handle options only AP_OPT_VARIANT of the FIRST item's
+ * handle is looked at (AP_VARIANT_TILE forces the matrix-core kernel on tiles when K % 256 == 0, any
+ * other value than AP_VARIANT_AUTO keeps the launch on the ALU kernel).  batch 1..8 here.  Same argument
+ * rules and error codes as ap_gemv.
  */
 typedef struct {
     const ap_matrix *h;

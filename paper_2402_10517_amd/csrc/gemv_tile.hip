@@ -62,10 +62,11 @@ template <int B> struct TileTable {
     }
 };
 
+// `wg` = index of the workgroup within its matrix (R tiles each).
 template <int B, int R, int MAXT>
-__global__ __launch_bounds__(MAXT) void gemv_tile_kernel(
-    const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
-    const uint16_t *__restrict__ x, uint16_t *__restrict__ y, int M, int K, int batch)
+__device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slices, size_t slice_bytes, const uint16_t *__restrict__ lut,
+                                               const uint16_t *__restrict__ x, uint16_t *__restrict__ y, int M, int K, int batch,
+                                               int wg)
 {
     using TT = TileTable<B>;
     constexpr int kTileRows = 16, kTileGroups = kTileRows / kRowsPerGroup;
@@ -83,7 +84,7 @@ __global__ __launch_bounds__(MAXT) void gemv_tile_kernel(
     const int i = lane & 15;  // row of a tile this lane dequantises; output column (batch row) it receives
     const int kg = lane >> 4; // its 8 columns of every instruction; its chunk of every quad of chunks
     const int groups = (M + kRowsPerGroup - 1) / kRowsPerGroup;
-    const int g0 = blockIdx.x * (R * kTileGroups);
+    const int g0 = wg * (R * kTileGroups);
     const int row0 = g0 * kRowsPerGroup;
     const int chunks = K / kChunkSlots;
     const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
@@ -328,6 +329,28 @@ __global__ __launch_bounds__(MAXT) void gemv_tile_kernel(
     }
 }
 
+template <int B, int R, int MAXT>
+__global__ __launch_bounds__(MAXT) void gemv_tile_kernel(const uint8_t *__restrict__ slices, size_t slice_bytes,
+                                                         const uint16_t *__restrict__ lut, const uint16_t *__restrict__ x,
+                                                         uint16_t *__restrict__ y, int M, int K, int batch)
+{
+    gemv_tile_body<B, R, MAXT>(slices, slice_bytes, lut, x, y, M, K, batch, (int)blockIdx.x);
+}
+
+// Several matrices of equal row length at one bit-width and batch in one launch (the projections of a
+// decoder layer that share their input): workgroup -> (matrix, tile) through the prefix sums of the
+// tile counts, which the launcher puts into group_begin.
+template <int B, int MAXT>
+__global__ __launch_bounds__(MAXT) void gemv_tile_multi_kernel(MultiArgs a)
+{
+    int m = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxMulti; ++i)
+        if (i < a.count && (int)blockIdx.x >= a.group_begin[i]) m = i;
+    gemv_tile_body<B, 1, MAXT>(a.slices[m], a.slice_bytes[m], a.lut[m], a.x[m], a.y[m], a.M[m], a.K, a.batch,
+                               (int)blockIdx.x - a.group_begin[m]);
+}
+
 template <int B, int R> static hipError_t launch_tile_r(const GemvArgs &a, hipStream_t stream)
 {
     constexpr int kMaxWaves = 8;
@@ -348,6 +371,36 @@ template <int B> static hipError_t launch_tile_b(const GemvArgs &a, hipStream_t 
     const int r = a.variant == 9 ? 1 : a.variant == 10 ? 2 : a.K >= 16384 ? 2 : 1;
     if (r == 2) return launch_tile_r<B, 2>(a, stream);
     return launch_tile_r<B, 1>(a, stream);
+}
+
+template <int B> static hipError_t launch_tile_multi_b(MultiArgs &m, int total_tiles, hipStream_t stream)
+{
+    constexpr int kMaxWaves = 8;
+    const int npairs = (m.K / (8 * kChunkSlots) + 1) / 2;
+    int nw = m.K >= 12288 ? kMaxWaves : 4;
+    if (nw > npairs) nw = npairs;
+    hipLaunchKernelGGL((gemv_tile_multi_kernel<B, 64 * kMaxWaves>), dim3(total_tiles), dim3(64 * nw), 0, stream, m);
+    return hipGetLastError();
+}
+
+// batch 2..8, K % 256 == 0 (the caller checks); one tile per workgroup
+hipError_t launch_matrix_tile_multi(const MultiArgs &a, int b, hipStream_t stream)
+{
+    MultiArgs m = a;
+    int total = 0;
+    for (int i = 0; i < m.count; ++i) {
+        m.group_begin[i] = total;
+        total += (m.M[i] + 15) / 16;
+    }
+    switch (b) {
+    case 3: return launch_tile_multi_b<3>(m, total, stream);
+    case 4: return launch_tile_multi_b<4>(m, total, stream);
+    case 5: return launch_tile_multi_b<5>(m, total, stream);
+    case 6: return launch_tile_multi_b<6>(m, total, stream);
+    case 7: return launch_tile_multi_b<7>(m, total, stream);
+    case 8: return launch_tile_multi_b<8>(m, total, stream);
+    }
+    return hipErrorInvalidValue;
 }
 
 // batch <= 8, K % 256 == 0 (the dispatcher checks)

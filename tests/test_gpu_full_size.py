@@ -51,6 +51,28 @@ def test_config2_and_3_shapes_sampled_rows_at_batch_3_to_8(B, M, K):
     pm.close()
 
 
+@pytest.mark.parametrize("batch", [4, 8])
+def test_fused_projections_of_a_7b_layer_at_small_batch(B, batch):
+    # q, k, v in one launch and gate, up in one launch, as the library chooses (the tile kernel)
+    import torch
+    rng = np.random.default_rng(5)
+    for (M, K, n) in [(4096, 4096, 3), (11008, 4096, 2)]:
+        mats = []
+        for k in range(n):
+            idx, luts, x = inputs.make_case(4, M, K, batch=batch, salt=k)
+            mats.append((idx, luts, B.ap_pack(idx, luts)))
+        xd = torch.from_numpy(x).cuda()
+        rows = np.unique(np.concatenate([np.arange(0, 20), np.arange(M - 20, M), rng.integers(0, M, size=128)]))
+        for b in (3, 5, 8):
+            triples = [(pm, xd, torch.empty((batch, M), dtype=torch.float16, device="cuda")) for (_, _, pm) in mats]
+            B.ap_gemv_multi(triples, b)
+            torch.cuda.synchronize()
+            for (idx, luts, pm), (_, _, y) in zip(mats, triples):
+                check_against_oracle(y.cpu().numpy(), idx, luts[b], b, x, rows=rows)
+        for m in mats:
+            m[2].close()
+
+
 @pytest.mark.parametrize("M,K", inputs.CONFIGS[5]["shapes"])
 def test_config5_llama70b_shapes_every_row_at_batch_1_sampled_rows_at_batch_2_to_8(B, M, K):
     idx, luts, x = inputs.make_case(5, M, K, batch=8, sigma=0.01)

@@ -316,6 +316,41 @@ def test_fused_launch_equals_separate_calls(B, batch):
     other.close()
 
 
+@pytest.mark.parametrize("batch", [2, 3, 5, 8])
+def test_fused_launch_on_the_tile_kernel(B, batch):
+    # forced through the first handle (the library chooses it from 1024 row groups per launch on): rows not
+    # a multiple of 16, a matrix smaller than a tile, a ragged last span, canaries around every output
+    import torch
+    K = 2048 + 768
+    mats = []
+    for k, M in enumerate([70, 37, 130, 8, 16]):
+        idx, luts, x = inputs.make_case(31, M, K, batch=batch, salt=k)
+        mats.append((idx, luts, x, B.ap_pack(idx, luts)))
+    mats[0][3].set_options(variant=B.VARIANT_TILE)
+    shared_x = torch.from_numpy(mats[0][2]).cuda()
+    guard = 32
+    for b in ALL_BITS:
+        for count in (1, 3, 5):
+            triples, bufs = [], []
+            for (idx, luts, x, pm) in mats[:count]:
+                buf = torch.full((guard + batch * pm.M + guard,), -3.0, dtype=torch.float16, device="cuda")
+                bufs.append(buf)
+                triples.append((pm, shared_x, buf[guard:guard + batch * pm.M].view(batch, pm.M)))
+            B.ap_gemv_multi(triples, b)
+            torch.cuda.synchronize()
+            for (idx, luts, x, pm), buf in zip(mats[:count], bufs):
+                out = buf.cpu().numpy()
+                assert np.all(out[:guard] == -3.0) and np.all(out[-guard:] == -3.0)
+                check_against_oracle(out[guard:-guard].reshape(batch, pm.M), idx, luts[b], b, mats[0][2])
+                # the same arithmetic as a single call on the tile kernel: bit-identical
+                pm.set_options(variant=B.VARIANT_TILE)
+                sep = B.ap_gemv(pm, b, shared_x)
+                torch.cuda.synchronize()
+                assert np.array_equal(out[guard:-guard].reshape(batch, pm.M).view(np.uint16), sep.cpu().numpy().view(np.uint16))
+    for m in mats:
+        m[3].close()
+
+
 def test_work_list_mixed_shapes_and_bit_widths(B):
     # one launch per 32 items: 40 items of 7 different shapes (1..9 spans, ragged spans, rows not a
     # multiple of 4), each with its own bit-width; every output bit-identical to a separate ap_gemv
