@@ -104,7 +104,7 @@ def large_batch(args, np, torch, B, inputs, dev):
                           rows=rows)))
 
 
-def decode_step_rows(np, torch, B, inputs, dev, modes, replays):
+def decode_step_rows(np, torch, B, inputs, dev, modes, replays, batch=1):
     """Config 4: all 224 matrices of a 7B-shaped model resident, one bit-width per decode step.
 
     Layer 0's seven matrices are drawn and packed; the other 31 layers are device copies of them
@@ -116,16 +116,17 @@ def decode_step_rows(np, torch, B, inputs, dev, modes, replays):
                   down (4 calls per layer; respects the data dependencies inside a real decoder layer)
       layer_list  one ap_gemv_list call per layer (7 matrices; config 4 treats the products as independent)
       list32      ap_gemv_list calls of 32 matrices (7 calls per step)
+    `batch` > 1 (modes separate and fused only): the same step for `batch` tokens at once.
     Returns {mode: [row per bit-width]}.
     """
     layer = []
     for k, (M, K) in enumerate(inputs.DECODE_LAYER_SHAPES):
-        idx, luts, x = inputs.make_case(4, M, K, salt=k)
+        idx, luts, x = inputs.make_case(4, M, K, salt=k, batch=batch)
         pm = B.ap_pack(idx, luts, device=dev)
         layer.append((M, K, pm, torch.from_numpy(x).to(dev)))
     model = [[(M, K, pm if l == 0 else pm.clone(), xd) for (M, K, pm, xd) in layer]
              for l in range(inputs.DECODE_LAYERS)]
-    youts = [[torch.empty((1, M), dtype=torch.float16, device=dev) for (M, K, pm, xd) in lay] for lay in model]
+    youts = [[torch.empty((batch, M), dtype=torch.float16, device=dev) for (M, K, pm, xd) in lay] for lay in model]
     cap = torch.cuda.Stream()
     sp = ctypes.c_void_p(cap.cuda_stream)
     fused_items = [B.make_items([(lay[i][2], lay[i][3], ys[i]) for i in grp])
@@ -140,11 +141,11 @@ def decode_step_rows(np, torch, B, inputs, dev, modes, replays):
         if mode == "separate":
             for lay, ys in zip(model, youts):
                 for (M, K, pm, xd), y in zip(lay, ys):
-                    if B.lib.ap_gemv(pm.handle, b, xd.data_ptr(), y.data_ptr(), 1, sp) != 0:
+                    if B.lib.ap_gemv(pm.handle, b, xd.data_ptr(), y.data_ptr(), batch, sp) != 0:
                         raise RuntimeError("ap_gemv failed")
         elif mode == "fused":
             for arr in fused_items:
-                if B.lib.ap_gemv_multi(arr, len(arr), b, 1, sp) != 0:
+                if B.lib.ap_gemv_multi(arr, len(arr), b, batch, sp) != 0:
                     raise RuntimeError("ap_gemv_multi failed")
         else:
             for arr in lists[(mode, b)]:
@@ -177,7 +178,7 @@ def decode_step_rows(np, torch, B, inputs, dev, modes, replays):
             per_b[b].append(e0.elapsed_time(e1) * 1e3)
         rows = []
         for b in range(3, 9):
-            nbytes = inputs.DECODE_LAYERS * sum(inputs.algorithmic_bytes(M, K, b) for (M, K) in inputs.DECODE_LAYER_SHAPES)
+            nbytes = inputs.DECODE_LAYERS * sum(inputs.algorithmic_bytes(M, K, b, batch) for (M, K) in inputs.DECODE_LAYER_SHAPES)
             us = float(np.median(per_b[b]))
             rows.append(dict(b=b, steps=len(per_b[b]), us_per_step=round(us, 1), bytes=nbytes,
                              GBps=round(nbytes / us / 1e3, 1), frac_of_peak=round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)))
@@ -525,6 +526,10 @@ def main():
                                              "batch 1; us per step by issue mode (fused = q,k,v | o | gate,up | down per "
                                              "layer; layer_list = one ap_gemv_list per layer; list32 = 32 matrices per call)",
                                     sequence=seq, per_bit_width=dec)
+        dec8, _ = decode_step_rows(np, torch, B, inputs, dev, ["separate", "fused"], 6, batch=8)
+        extra["decode_step_batch8"] = dict(workload="the same model and step for 8 tokens at once (batch 8): 224 ap_gemv calls, "
+                                                    "or ap_gemv_multi per group of equal row length (4 calls per layer)",
+                                           per_bit_width=dec8)
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload ------------------
     cpu = None
