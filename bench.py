@@ -116,7 +116,7 @@ def decode_step_rows(np, torch, B, inputs, dev, modes, replays, batch=1):
                   down (4 calls per layer; respects the data dependencies inside a real decoder layer)
       layer_list  one ap_gemv_list call per layer (7 matrices; config 4 treats the products as independent)
       list32      ap_gemv_list calls of 32 matrices (7 calls per step)
-    `batch` > 1 (modes separate and fused only): the same step for `batch` tokens at once.
+    `batch` > 1: the same step for `batch` tokens at once (the list modes then call ap_gemv_list_batch).
     Returns {mode: [row per bit-width]}.
     """
     layer = []
@@ -149,8 +149,8 @@ def decode_step_rows(np, torch, B, inputs, dev, modes, replays, batch=1):
                     raise RuntimeError("ap_gemv_multi failed")
         else:
             for arr in lists[(mode, b)]:
-                if B.lib.ap_gemv_list(arr, len(arr), sp) != 0:
-                    raise RuntimeError("ap_gemv_list failed")
+                if B.lib.ap_gemv_list_batch(arr, len(arr), batch, sp) != 0:
+                    raise RuntimeError("ap_gemv_list_batch failed")
 
     seq = inputs.decode_bit_sequence(replays)
     results = {}
@@ -526,9 +526,10 @@ def main():
                                              "batch 1; us per step by issue mode (fused = q,k,v | o | gate,up | down per "
                                              "layer; layer_list = one ap_gemv_list per layer; list32 = 32 matrices per call)",
                                     sequence=seq, per_bit_width=dec)
-        dec8, _ = decode_step_rows(np, torch, B, inputs, dev, ["separate", "fused"], 6, batch=8)
+        dec8, _ = decode_step_rows(np, torch, B, inputs, dev, ["separate", "fused", "list32"], 6, batch=8)
         extra["decode_step_batch8"] = dict(workload="the same model and step for 8 tokens at once (batch 8): 224 ap_gemv calls, "
-                                                    "or ap_gemv_multi per group of equal row length (4 calls per layer)",
+                                                    "ap_gemv_multi per group of equal row length (4 calls per layer), or "
+                                                    "ap_gemv_list_batch with 32 matrices per call",
                                            per_bit_width=dec8)
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload ------------------

@@ -202,6 +202,21 @@ typedef struct {
 ap_status ap_gemv_list(const ap_gemv_list_item *items, int count, void *stream);
 
 /*
+ * The same work list for `batch` activation rows per item (1 <= batch <= 8): y_i (batch x M_i) =
+ * x_i (batch x K_i) * W_i,b_i^T, the decode step of `batch` queries that run at the same precision
+ * (Section 6.2 measures the kernel up to batch 8).  batch 1 is ap_gemv_list.  At batch >= 2 the items
+ * that the matrix-core kernel on tiles of 16 rows can take (K_i % 256 == 0) are launched together per
+ * bit-width and class of row length, up to 32 per launch, whenever such a group has at least 1024 row
+ * groups in total (the size rule of ap_gemv applied to the launch); every other item runs as its own
+ * ap_gemv call on the same stream.  Outputs meet the tolerance of ap_gemv; an item that runs on the tile
+ * kernel is bit-identical to ap_gemv on that kernel (AP_VARIANT_TILE) when every row of its launch has
+ * at least 2048 columns (shorter rows lower the number of waves per tile of the launch, which changes the
+ * order of the final sums).  Same argument rules as
+ * ap_gemv_list; x_dev of an item holds batch * K_i, y_dev batch * M_i values.
+ */
+ap_status ap_gemv_list_batch(const ap_gemv_list_item *items, int count, int batch, void *stream);
+
+/*
  * Dense binary16 weights of the b-bit model: w_dev[i*K + j] = C_b[i][ idx[i][j] >> (n-b) ], bit for
  * bit the table entries (Section 6.2, "Matrix-Matrix Multiplication Performance": for large batches
  * the engine dequantises with a separate kernel and uses a dense FP16 GEMM).

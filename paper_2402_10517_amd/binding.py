@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "AP_OK", 1: "AP_ERR_INVALID_ARG", 2: "AP_ERR_SHAPE", 3: "AP_E
                 7: "AP_ERR_HIP", 8: "AP_ERR_NO_MEMORY"}
 
 EXPORTS = ["ap_packed_size", "ap_pack_host", "ap_unpack_host", "ap_blob_lut_entry",
-           "ap_read_extent", "ap_pack", "ap_attach", "ap_set_option", "ap_unpack", "ap_gemv", "ap_gemv_multi", "ap_gemv_list", "ap_dequantize",
+           "ap_read_extent", "ap_pack", "ap_attach", "ap_set_option", "ap_unpack", "ap_gemv", "ap_gemv_multi", "ap_gemv_list", "ap_gemv_list_batch", "ap_dequantize",
            "ap_gemm_workspace_size", "ap_gemm", "ap_gemm_static", "ap_quantize", "ap_probe_read", "ap_matrix_info",
            "ap_free", "ap_strerror"]
 
@@ -58,6 +58,7 @@ def _load():
     L.ap_gemv.argtypes = [vp, ci, vp, vp, ci, vp]
     L.ap_gemv_multi.argtypes = [vp, ci, ci, ci, vp]
     L.ap_gemv_list.argtypes = [vp, ci, vp]
+    L.ap_gemv_list_batch.argtypes = [vp, ci, ci, vp]
     L.ap_dequantize.argtypes = [vp, ci, vp, vp]
     L.ap_gemm_workspace_size.argtypes = [vp, psz]
     L.ap_gemm.argtypes = [vp, ci, vp, vp, ci, vp, sz, vp]
@@ -244,6 +245,14 @@ def ap_gemv_list(quads, stream=None):
     arr = make_list(quads)
     sp, _ = _stream_ptr(stream)
     _check(lib.ap_gemv_list(arr, len(quads), sp), "ap_gemv_list")
+    return [q[3] for q in quads]
+
+
+def ap_gemv_list_batch(quads, batch, stream=None):
+    """Work list for `batch` activation rows per item: quads = [(PackedMatrix, b, x (batch, K), y (batch, M)), ...]."""
+    arr = make_list(quads)
+    sp, _ = _stream_ptr(stream)
+    _check(lib.ap_gemv_list_batch(arr, len(quads), int(batch), sp), "ap_gemv_list_batch")
     return [q[3] for q in quads]
 
 

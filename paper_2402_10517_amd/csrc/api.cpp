@@ -257,6 +257,62 @@ extern "C" ap_status ap_gemv_list(const ap_gemv_list_item *items, int count, voi
     return AP_OK;
 }
 
+extern "C" ap_status ap_gemv_list_batch(const ap_gemv_list_item *items, int count, int batch, void *stream)
+{
+    if (batch == 1) return ap_gemv_list(items, count, stream);
+    if (!items || count < 1) return AP_ERR_INVALID_ARG;
+    if (batch < 1 || batch > AP_MAX_MULTI_BATCH) return AP_ERR_BATCH;
+    ListItem probe;
+    for (int i = 0; i < count; ++i) { // every item is checked before anything is enqueued
+        ap_status s = fill_list_item(items[i].h, items[i].b, items[i].x_dev, items[i].y_dev, &probe);
+        if (s != AP_OK) return s;
+    }
+    // Groups of items the tile kernel takes together: same bit-width, same class of row length; an item
+    // whose handle carries a tuning override runs on its own.  Three passes over the list, no allocation.
+    auto group_of = [](const ap_gemv_list_item &it, int *b, int *cls) {
+        const ap_matrix *h = it.h;
+        const bool plain = h->variant == AP_VARIANT_AUTO && h->waves_per_group == 0 && h->row_groups_per_wg < 0 &&
+                           h->mfma_min_batch == 0;
+        if (h->hdr.K % 256 != 0 || !plain) return false;
+        *b = it.b;
+        *cls = h->hdr.K >= 12288 ? 1 : 0;
+        return true;
+    };
+    int members[AP_MAX_BITS + 1][2] = {};
+    long long row_groups[AP_MAX_BITS + 1][2] = {};
+    for (int i = 0; i < count; ++i) {
+        int gb, gc;
+        if (!group_of(items[i], &gb, &gc)) continue;
+        ++members[gb][gc];
+        row_groups[gb][gc] += padded_rows(items[i].h->hdr.M) / kRowsPerGroup;
+    }
+    auto together = [&](int gb, int gc) { return members[gb][gc] >= 2 && row_groups[gb][gc] >= 1024; };
+    for (int gb = AP_MIN_BITS; gb <= AP_MAX_BITS; ++gb)
+        for (int gc = 0; gc < 2; ++gc) {
+            if (!together(gb, gc)) continue;
+            ListArgs la;
+            std::memset(&la, 0, sizeof(la));
+            for (int i = 0; i < count; ++i) {
+                int ib, ic;
+                if (!group_of(items[i], &ib, &ic) || ib != gb || ic != gc) continue;
+                fill_list_item(items[i].h, gb, items[i].x_dev, items[i].y_dev, &la.item[la.count++]);
+                if (la.count == kMaxListItems) {
+                    if (launch_matrix_tile_list(la, gb, batch, static_cast<hipStream_t>(stream)) != hipSuccess) return AP_ERR_HIP;
+                    la.count = 0;
+                }
+            }
+            if (la.count > 0 && launch_matrix_tile_list(la, gb, batch, static_cast<hipStream_t>(stream)) != hipSuccess)
+                return AP_ERR_HIP;
+        }
+    for (int i = 0; i < count; ++i) {
+        int ib, ic;
+        if (group_of(items[i], &ib, &ic) && together(ib, ic)) continue;
+        ap_status s = ap_gemv(items[i].h, items[i].b, items[i].x_dev, items[i].y_dev, batch, stream);
+        if (s != AP_OK) return s;
+    }
+    return AP_OK;
+}
+
 extern "C" ap_status ap_gemv_multi(const ap_gemv_item *items, int count, int b, int batch, void *stream)
 {
     if (!items || count < 1 || count > kMaxMulti) return AP_ERR_INVALID_ARG;

@@ -351,6 +351,18 @@ __global__ __launch_bounds__(MAXT) void gemv_tile_multi_kernel(MultiArgs a)
                                (int)blockIdx.x - a.group_begin[m]);
 }
 
+// A work list of matrices of any shapes (rows of one class of length) at one bit-width and batch.
+template <int B, int MAXT>
+__global__ __launch_bounds__(MAXT) void gemv_tile_list_kernel(ListArgs a, int batch)
+{
+    int it = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxListItems; ++i)
+        if (i < a.count && (int)blockIdx.x >= a.group_begin[i]) it = i;
+    const ListItem &I = a.item[it];
+    gemv_tile_body<B, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, I.K, batch, (int)blockIdx.x - a.group_begin[it]);
+}
+
 template <int B, int R> static hipError_t launch_tile_r(const GemvArgs &a, hipStream_t stream)
 {
     constexpr int kMaxWaves = 8;
@@ -399,6 +411,37 @@ hipError_t launch_matrix_tile_multi(const MultiArgs &a, int b, hipStream_t strea
     case 6: return launch_tile_multi_b<6>(m, total, stream);
     case 7: return launch_tile_multi_b<7>(m, total, stream);
     case 8: return launch_tile_multi_b<8>(m, total, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <int B> static hipError_t launch_tile_list_b(const ListArgs &a, int total_tiles, int nw, int batch, hipStream_t stream)
+{
+    hipLaunchKernelGGL((gemv_tile_list_kernel<B, 512>), dim3(total_tiles), dim3(64 * nw), 0, stream, a, batch);
+    return hipGetLastError();
+}
+
+hipError_t launch_matrix_tile_list(ListArgs &a, int b, int batch, hipStream_t stream)
+{
+    int total = 0, min_pairs = 1 << 30;
+    bool long_rows = false;
+    for (int i = 0; i < a.count; ++i) {
+        a.group_begin[i] = total;
+        total += (a.item[i].M + 15) / 16;
+        const int npairs = (a.item[i].K / (8 * kChunkSlots) + 1) / 2;
+        if (npairs < min_pairs) min_pairs = npairs;
+        long_rows = a.item[i].K >= 12288;
+    }
+    for (int i = a.count; i < kMaxListItems; ++i) a.group_begin[i] = 0x7fffffff;
+    int nw = long_rows ? 8 : 4; // as in single calls; no more waves than the shortest row has pairs of octets
+    if (nw > min_pairs) nw = min_pairs;
+    switch (b) {
+    case 3: return launch_tile_list_b<3>(a, total, nw, batch, stream);
+    case 4: return launch_tile_list_b<4>(a, total, nw, batch, stream);
+    case 5: return launch_tile_list_b<5>(a, total, nw, batch, stream);
+    case 6: return launch_tile_list_b<6>(a, total, nw, batch, stream);
+    case 7: return launch_tile_list_b<7>(a, total, nw, batch, stream);
+    case 8: return launch_tile_list_b<8>(a, total, nw, batch, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -60,6 +60,9 @@ hipError_t launch_gemv_list(ListArgs &a, hipStream_t stream);
 hipError_t launch_gemv_multi(const MultiArgs &a, int b, int total_groups, hipStream_t stream);
 // the same launch on the matrix-core kernel over tiles of 16 rows (batch 2..8, K % 256 == 0)
 hipError_t launch_matrix_tile_multi(const MultiArgs &a, int b, hipStream_t stream);
+// a work list on that kernel: every item at bit-width b, K % 256 == 0, all rows in the same class of length
+// (below / from 12288 columns); group_begin is filled in here
+hipError_t launch_matrix_tile_list(ListArgs &a, int b, int batch, hipStream_t stream);
 hipError_t launch_dequantize(const GemvArgs &a, hipStream_t stream);
 hipError_t launch_probe_read(const void *dev_buf, size_t bytes, hipStream_t stream);
 // Looks up, once per device, the device address of the static array ap_gemm_static writes the dense

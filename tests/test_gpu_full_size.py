@@ -73,6 +73,28 @@ def test_fused_projections_of_a_7b_layer_at_small_batch(B, batch):
             m[2].close()
 
 
+def test_config4_one_layer_as_a_batched_work_list(B):
+    # the seven matrices of a decoder layer at batch 8 in one call: the 4096-column ones share a launch of
+    # the tile kernel, 4096x11008 runs on its own
+    import torch
+    batch, b = 8, 4
+    rng = np.random.default_rng(9)
+    mats, quads = [], []
+    for k, (M, K) in enumerate(inputs.DECODE_LAYER_SHAPES):
+        idx, luts, x = inputs.make_case(4, M, K, batch=batch, salt=k)
+        pm = B.ap_pack(idx, luts)
+        y = torch.empty((batch, M), dtype=torch.float16, device="cuda")
+        mats.append((idx, luts, x, pm, y))
+        quads.append((pm, b, torch.from_numpy(x).cuda(), y))
+    B.ap_gemv_list_batch(quads, batch)
+    torch.cuda.synchronize()
+    for (idx, luts, x, pm, y) in mats:
+        M = pm.M
+        rows = np.unique(np.concatenate([np.arange(0, 20), np.arange(M - 20, M), rng.integers(0, M, size=128)]))
+        check_against_oracle(y.cpu().numpy(), idx, luts[b], b, x, rows=rows)
+        pm.close()
+
+
 @pytest.mark.parametrize("M,K", inputs.CONFIGS[5]["shapes"])
 def test_config5_llama70b_shapes_every_row_at_batch_1_sampled_rows_at_batch_2_to_8(B, M, K):
     idx, luts, x = inputs.make_case(5, M, K, batch=8, sigma=0.01)

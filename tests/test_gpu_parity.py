@@ -351,6 +351,56 @@ def test_fused_launch_on_the_tile_kernel(B, batch):
         m[3].close()
 
 
+@pytest.mark.parametrize("batch", [2, 5, 8])
+def test_batched_work_list(B, batch):
+    # items of several shapes and bit-widths: groups large enough for the tile kernel (same b, rows of one
+    # class of length, >= 1024 row groups together) share a launch, the others run as single calls;
+    # canaries around every output; a tile-kernel item is bit-identical to the single call on that kernel
+    import ctypes
+    import torch
+    shapes = [(2100, 2048), (2050, 2304), (37, 256), (70, 2048 + 96), (2060, 12288), (2100, 12288 + 256), (16, 12544)]
+    mats = []
+    for k, (M, K) in enumerate(shapes):
+        idx, luts, x = inputs.make_case(33, M, K, batch=batch, salt=k, bit_widths=[3, 4, 8], sigma=0.01)
+        mats.append((idx, luts, x, B.ap_pack(idx, luts), torch.from_numpy(x).cuda()))
+    guard = 32
+    quads, bufs, meta = [], [], []
+    for rep, bsel in enumerate([(3, 3, 4, 3, 4, 4, 4), (8, 8, 4, 8, 4, 4, 3)]):
+        for (idx, luts, x, pm, xd), b in zip(mats, bsel):
+            buf = torch.full((guard + batch * pm.M + guard,), -5.0, dtype=torch.float16, device="cuda")
+            bufs.append(buf)
+            quads.append((pm, b, xd, buf[guard:guard + batch * pm.M].view(batch, pm.M)))
+            meta.append((idx, luts, x, pm, xd, b))
+    B.ap_gemv_list_batch(quads, batch)
+    torch.cuda.synchronize()
+    for (idx, luts, x, pm, xd, b), buf in zip(meta, bufs):
+        out = buf.cpu().numpy()
+        assert np.all(out[:guard] == -5.0) and np.all(out[-guard:] == -5.0)
+        y = out[guard:-guard].reshape(batch, pm.M)
+        check_against_oracle(y, idx, luts[b], b, x)
+    # the first two items of the first half (b = 3, 2048 and 2304 columns: 1038 row groups together) ran on
+    # the tile kernel with 4 waves per tile, like a single call on it
+    for k in (0, 1):
+        idx, luts, x, pm, xd, b = meta[k]
+        pm.set_options(variant=B.VARIANT_TILE)
+        sep = B.ap_gemv(pm, b, xd)
+        torch.cuda.synchronize()
+        assert np.array_equal(bufs[k].cpu().numpy()[guard:-guard].reshape(batch, pm.M).view(np.uint16),
+                              sep.cpu().numpy().view(np.uint16))
+        pm.set_options(variant=B.VARIANT_AUTO)
+    # argument checks: status of the first bad item, nothing enqueued; batch range
+    bad = list(quads)
+    bad[3] = (quads[3][0], 5, quads[3][2], quads[3][3])       # no table for b = 5
+    with pytest.raises(B.ApError) as e:
+        B.ap_gemv_list_batch(bad, batch)
+    assert e.value.status == 3
+    with pytest.raises(B.ApError) as e:
+        B.ap_gemv_list_batch(quads, 9)
+    assert e.value.status == 6
+    for m in mats:
+        m[3].close()
+
+
 def test_work_list_mixed_shapes_and_bit_widths(B):
     # one launch per 32 items: 40 items of 7 different shapes (1..9 spans, ragged spans, rows not a
     # multiple of 4), each with its own bit-width; every output bit-identical to a separate ap_gemv
