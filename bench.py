@@ -312,9 +312,10 @@ def main():
     stream = torch.cuda.current_stream()
     sp = ctypes.c_void_p(stream.cuda_stream)
     if args.decode_step:
-        res, seq = decode_step_rows(np, torch, B, inputs, dev, ["separate", "fused", "layer_list", "list32"], 64)
-        print(json.dumps(dict(metric="7B-shaped decode step latency by bit-width (224 batch-1 GEMVs per step) per issue mode",
-                              unit="us/step", n_gpus=1, data="synthetic", sequence=seq, per_bit_width=res)))
+        res, seq = decode_step_rows(np, torch, B, inputs, dev, ["separate", "fused", "layer_list", "list32"],
+                                    64 if args.batch == 1 else 18, batch=args.batch)
+        print(json.dumps(dict(metric="7B-shaped decode step latency by bit-width (224 GEMVs of batch %d per step) per issue mode"
+                              % args.batch, unit="us/step", n_gpus=1, data="synthetic", sequence=seq, per_bit_width=res)))
         return
     if args.large_batch:
         large_batch(args, np, torch, B, inputs, dev)
