@@ -33,7 +33,7 @@ typedef enum {
     AP_ERR_BITS = 3,             /* n outside 3..8, b outside 3..n, or no table given for b */
     AP_ERR_INDEX_RANGE = 4,      /* an index >= 2^n */
     AP_ERR_BUFFER_TOO_SMALL = 5, /* destination smaller than ap_packed_size */
-    AP_ERR_BATCH = 6,            /* batch outside 1..16 (ap_gemv) or 1..8 (ap_gemv_multi) */
+    AP_ERR_BATCH = 6,            /* batch outside 1..16 (ap_gemv) or 1..8 (the multi and list calls) */
     AP_ERR_HIP = 7,              /* a HIP runtime call or kernel launch failed */
     AP_ERR_NO_MEMORY = 8         /* host memory (a handle, the pinned staging buffer) could not be allocated */
 } ap_status;
