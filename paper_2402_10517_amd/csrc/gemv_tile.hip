@@ -9,15 +9,17 @@
 //   * A wave works on octets of chunks (8 chunks = 256 columns of the tile's 16 rows): two quads of
 //     chunks, lane group kg taking chunk kg of the first and chunk 4 + kg of the second.
 //   * Every load instruction reads whole 128-byte lines in lane order.  A slice load covers 2 row groups
-//     x 8 chunks x 4 rows (lane 32 p + 4 c + r: group p, chunk c, row r), two loads per slice and tile;
-//     one v_permlane16_swap turns the pair into the words of the first and of the second quad (all 4
-//     row groups each), and one ds_bpermute per word moves a word to the lane that dequantises it
+//     x 8 chunks x 4 rows (lane 32 p + 4 c + r: group p, chunk c ^ 2 p, row r), two loads per slice and
+//     tile; one v_permlane16_swap turns the pair into the words of the first and of the second quad (all
+//     4 row groups each), and one ds_bpermute per word moves a word to the lane that dequantises it
 //     (lane 16 kg + 4 g + r: group g, row r).  Loaded directly in that order, every 4 lanes would touch
 //     another cache line and a line would be requested again while it is still in flight.
 //   * The activations of a run of an octet are 128 contiguous bytes per batch row: lane 8 n + p loads
-//     the 16 bytes of batch row n for chunk p, so one instruction covers 8 batch rows line by line (a
-//     lane-per-row order costs one cache access per lane).  Four ds_bpermute per run move them to the
-//     lanes of the matrix instruction: lane (i, kg) takes batch row i % 8, chunk 4 (i / 8) + kg.  Both
+//     16 bytes of batch row n (chunk p ^ 2 (n / 4)), so one instruction covers 8 batch rows line by line
+//     (a lane-per-row order costs one cache access per lane).  Four ds_bpermute per run move them to the
+//     lanes of the matrix instruction: lane (i, kg) takes batch row i % 8, chunk 4 (i / 8) + kg.  The
+//     chunk exchanges (^ 2 p, ^ 2 (n / 4)) make the 32 source lanes of each half of a ds_bpermute
+//     different mod 32, which is what that instruction needs to run without bank conflicts.  Both
 //     quads of the octet use that register as B: output columns 0..7 of the first quad's instruction
 //     and columns 8..15 of the second's are the products wanted (batch rows 0..7 each), the other
 //     halves multiply one quad's weights with the other quad's activations and are dropped, so each
@@ -90,8 +92,9 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
     const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
 
     // ---- per-lane offsets of the slice loads: lane 32 p + 4 c + r loads row r of row group 2 half + p of
-    // the tile, chunk c of the octet
-    const int lp = lane >> 5, lc = (lane >> 2) & 7, lr = lane & 3;
+    // the tile, chunk c ^ 2 p of the octet (16 lanes still read 64 contiguous bytes; the exchange of the
+    // chunk pairs in the odd row groups keeps the lane exchange below free of bank conflicts)
+    const int lp = lane >> 5, lc = ((lane >> 2) & 7) ^ (lp << 1), lr = lane & 3;
     const __amdgpu_buffer_rsrc_t srsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(slices + (size_t)g0 * chunks * 16), 0, 0xffffffffu, kBufferRsrcWord3);
     uint32_t soff_lane[R][2];
@@ -103,19 +106,23 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
             if (g0 + rg >= groups) rg = groups - 1 - g0; // past the matrix: the last group again (never stored)
             soff_lane[tile][half] = (uint32_t)(rg * chunks + lc) * 16u + (uint32_t)lr * 4u;
         }
-    // After the swap of 16-lane rows, lane 16 p + 4 c + r of the first (second) word holds row r, chunk c
-    // (4 + c) of the row group at position p of the order 0, 2, 1, 3; this lane dequantises row i & 3 of
-    // row group i >> 2, chunk kg (4 + kg).
-    const int bperm_src = (((((i >> 2) & 1) << 1 | (i >> 3)) << 4) | (kg << 2) | (i & 3)) << 2; // byte address of the source lane
-    // activations: lane 8 n + p loads batch row n, chunk p of the octet; the descriptor ends with the last
-    // batch row, and lanes of rows past the batch carry an offset beyond it (batch * K * 2 < 2^31; valid
-    // lanes stay below the end with any scalar offset).  This lane then takes batch row i & 7, chunk
-    // 4 (i >> 3) + kg.
+    // After the swap of 16-lane rows, lane 16 p + 4 c + r of the first (second) word holds row r, chunk
+    // c ^ 2 (g & 1) (plus 4) of the row group g at position p of the order 0, 2, 1, 3; this lane
+    // dequantises row i & 3 of row group i >> 2, chunk kg (4 + kg).  ds_bpermute serves 32 lanes a clock
+    // and two of them conflict when their source lanes are equal mod 32: with the chunk exchange the 32
+    // sources of either half of the wave are all different (without it every exchange took two clocks
+    // more).
+    const int bperm_src = (((((i >> 2) & 1) << 1 | (i >> 3)) << 4) | ((kg ^ (((i >> 2) & 1) << 1)) << 2) | (i & 3)) << 2; // byte address of the source lane
+    // activations: lane 8 n + p loads batch row n, chunk p ^ 2 (n / 4) of the octet (8 lanes = one 128-byte
+    // line; the exchange for the same reason as above); the descriptor ends with the last batch row, and
+    // lanes of rows past the batch carry an offset beyond it (batch * K * 2 < 2^31; valid lanes stay below
+    // the end with any scalar offset).  This lane then takes batch row i & 7, chunk 4 (i >> 3) + kg.
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(x), 0, (uint32_t)batch * (uint32_t)K * 2u, kBufferRsrcWord3);
-    const uint32_t xoff_lane =
-        (lane >> 3) < batch ? (uint32_t)(lane >> 3) * (uint32_t)K * 2u + (uint32_t)(lane & 7) * 16u : 0x80000000u;
-    const int xperm_src = (((i & 7) << 3) | ((i >> 3) << 2) | kg) << 2; // byte address of the source lane
+    const uint32_t xoff_lane = (lane >> 3) < batch ? (uint32_t)(lane >> 3) * (uint32_t)K * 2u +
+                                                         (uint32_t)((lane & 7) ^ ((lane >> 5) << 1)) * 16u
+                                                   : 0x80000000u;
+    const int xperm_src = (((i & 7) << 3) | ((i >> 3) << 2) | (kg ^ (((i >> 2) & 1) << 1))) << 2; // byte address of the source lane
     const uint32_t rowbase = ((uint32_t)i << 2) | ((uint32_t)(kg & 1) << 6);
 
     float4_t acc[R][2]; // one accumulator per quad of an octet: independent chains of matrix instructions
