@@ -35,7 +35,7 @@ __device__ __forceinline__ uint32_t bitsel(uint32_t m, uint32_t a, uint32_t b)
     asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(d) : "s"(m), "v"(a), "v"(b));
     return d;
 }
-// (byte J of v) & mask, and (byte J of v) << 1: one SDWA instruction each.  They turn a byte of a
+// (byte J of v) & mask, and (byte J of v) << n with n in a register: one SDWA instruction each.  They turn a byte of a
 // merged index word into an LDS address.
 template <int J> __device__ __forceinline__ uint32_t byte_and(uint32_t v, uint32_t mask)
 {
@@ -363,6 +363,31 @@ __device__ __forceinline__ void compute_unit(const u32x4 (&Q)[B], const u32x4 (&
         }
     }
 }
+
+// ---- 4 bits, two weights per lookup (Section 5.3 "Merging Table Lookups", one bit-width further; used by the
+// tile kernel, where a lane's row owns an LDS bank and the 256-entry table of a row gathers without the
+// random bank conflicts it meets when all lanes of a wave read one row's table).  Slice 3 (rotation 3) is
+// rotated to rotation 0 first, so that all four slices sit at even rotations {6, 4, 2, 0} and the bit of the
+// odd slot of a pair, one position higher, never meets another slice: byte j of W[u] (u even) is the pair
+// index of slots 8j + u and 8j + u + 1 with slice s of the even slot at bit 6 - 2s and of the odd slot at
+// bit 7 - 2s.  Only levels 2 and 3 of the select tree are left (8 selects, 1 + 3 rotates per 32 weights).
+__device__ __forceinline__ void merge_words_pair4(const uint32_t (&q)[4], uint32_t (&W)[8])
+{
+    const uint32_t q3 = rotr_v(q[3], 3);
+    uint32_t L2[2][2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        L2[0][c] = bitsel(rotl_c(0x33333333u, 2 * c), q3, q[2]);
+        L2[1][c] = bitsel(rotl_c(0x33333333u, 2 * c), q[1], q[0]);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; u += 2)
+        W[u] = rotr_v(bitsel(rotl_c(0x0F0F0F0Fu, u), L2[0][(u >> 1) & 1], L2[1][(u >> 1) & 1]), u);
+}
+// Positions in the stored 4-bit table (slice 0, 1, 3, 2 at bits 3, 2, 1, 0) of the even and the odd slot of
+// pair index p.
+__device__ __forceinline__ int pair4_even(int p) { return ((p >> 3) & 8) | ((p >> 2) & 4) | ((p << 1) & 2) | ((p >> 2) & 1); }
+__device__ __forceinline__ int pair4_odd(int p) { return ((p >> 4) & 8) | ((p >> 3) & 4) | (p & 2) | ((p >> 3) & 1); }
 
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));

@@ -35,7 +35,14 @@
 //     that one v_perm_b32 per lookup builds the address from the word's byte and the lane's base; for
 //     b = 8 that would need 64 KB per tile, so s = 7 and the address takes two operations (a byte
 //     select and a shift-or).  The 3-bit path keeps its 64-entry table of centroid pairs, one pair
-//     per dword.
+//     per dword.  The 4-bit path looks pairs up as well: slice 3 is rotated to rotation 0 so that a
+//     merged byte is the 8-bit index of a column pair (8 selects and 4 rotates per 32 weights instead
+//     of 14 and 7, no clean-up), a row's 256 pair entries are built in LDS from its 16 stored
+//     centroids, one copy, entry p of row i at (p << 6) | (i << 2) (two operations per address, but
+//     per pair, and no pack before the matrix instruction); a row still owns its bank, the two lane
+//     groups of a clock collide only when their indices have the same parity.  Here that pays (28672 x
+//     8192 at batch 8: 49 -> 45 us, 8192 x 28672: 48 -> 42); in the batch-1 kernel, where all 64 lanes
+//     gather from one row's 256 dwords, the bank conflicts eat the gain.
 // Requires K % 256 == 0 (an octet is entirely inside or outside a ragged last span) and batch <= 8.
 #include "device_common.h"
 #include "launchers.h"
@@ -44,13 +51,16 @@ namespace apgemv {
 
 template <int B> struct TileTable {
     static constexpr bool kPair = (B == 3);
+    // 4 bits: a 256-entry table of centroid pairs per row, one copy, entry p of row i at (p << 6) | (i << 2)
+    // (the two lane groups of a clock meet in a bank when their pair indices have the same parity)
+    static constexpr bool kPair4 = (B == 4);
     static constexpr uint32_t kMask = kPair ? 0xFCu : Table<B>::addr_mask(); // index bits inside a merged byte
     static constexpr int kLow = (kMask & 1) ? 0 : (kMask & 2) ? 1 : 2;       // lowest of them
     static constexpr bool kPerm = (B <= 7);                                  // address by one v_perm_b32
     static constexpr int kExtra = kPerm ? kLow : 0;                          // extra rotation of the index words
     static constexpr uint32_t kClean = (kMask >> kExtra) * 0x01010101u;      // index bits of the rotated words
     static constexpr int kShift = kPerm ? 8 : 7 - kLow;                      // entry value -> address
-    static constexpr int kTileBytes = (int)((kMask >> kLow) + 1) << (kPerm ? 8 : 7); // 16 rows x 2 copies x 4 bytes per entry (x 2 unused)
+    static constexpr int kTileBytes = kPair4 ? 256 * 64 : (int)((kMask >> kLow) + 1) << (kPerm ? 8 : 7); // 16 rows x 2 copies x 4 bytes per entry (x 2 unused)
     // value in a (rotated) index byte of the entry stored at position p of a row (lut_stored_pos order; pair index for B = 3)
     __device__ static constexpr uint32_t byte_of(uint32_t p)
     {
@@ -76,7 +86,7 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
     constexpr int kTabBytes = R * TT::kTileBytes, kRedBytes = (MAXT / 64) * R * kTileRows * 16 * 4;
     __shared__ __attribute__((aligned(16))) uint8_t smem[kTabBytes > kRedBytes ? kTabBytes : kRedBytes];
     uint8_t *tab = smem;
-    __shared__ __attribute__((aligned(16))) uint16_t nat[TT::kPair ? R * kTileRows * 8 : 8]; // natural rows (3-bit path)
+    __shared__ __attribute__((aligned(16))) uint16_t nat[TT::kPair ? R * kTileRows * 8 : TT::kPair4 ? R * kTileRows * 16 : 8]; // the rows as stored (pair paths)
     float(*red)[R][kTileRows][16] = reinterpret_cast<float(*)[R][kTileRows][16]>(smem);
 
     const int tid = threadIdx.x, nth = blockDim.x;
@@ -124,6 +134,9 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
                                                    : 0x80000000u;
     const int xperm_src = (((i & 7) << 3) | ((i >> 3) << 2) | (kg ^ (((i >> 2) & 1) << 1))) << 2; // byte address of the source lane
     const uint32_t rowbase = ((uint32_t)i << 2) | ((uint32_t)(kg & 1) << 6);
+    const uint32_t row4 = (uint32_t)i << 2; // pair path at 4 bits: one copy
+    uint32_t six = 6;                       // its shift amount, kept in a register (SDWA operand)
+    asm("" : "+v"(six));
 
     float4_t acc[R][2]; // one accumulator per quad of an octet: independent chains of matrix instructions
 #pragma unroll
@@ -171,9 +184,14 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
                     q[0][s] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm_src, (int)sw[0]);
                     q[1][s] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm_src, (int)sw[1]);
                 }
-                merge_words<B, TT::kExtra>(q[0], W[0]);
-                merge_words<B, TT::kExtra>(q[1], W[1]);
-                if constexpr (TT::kPerm) {
+                if constexpr (TT::kPair4) {
+                    merge_words_pair4(q[0], W[0]);
+                    merge_words_pair4(q[1], W[1]);
+                } else {
+                    merge_words<B, TT::kExtra>(q[0], W[0]);
+                    merge_words<B, TT::kExtra>(q[1], W[1]);
+                }
+                if constexpr (TT::kPerm && !TT::kPair4) {
 #pragma unroll
                     for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -183,15 +201,22 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 uint32_t P[2][4]; // packed centroid pairs: P[h][j] = columns 2j, 2j + 1 of run t, quad h
-                if constexpr (TT::kPair) {
+                if constexpr (TT::kPair || TT::kPair4) {
                     uint32_t ad[2][4];
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         const uint32_t v = W[h][2 * t];
-                        ad[h][0] = TT::template addr<0>(v, rowbase);
-                        ad[h][1] = TT::template addr<1>(v, rowbase);
-                        ad[h][2] = TT::template addr<2>(v, rowbase);
-                        ad[h][3] = TT::template addr<3>(v, rowbase);
+                        if constexpr (TT::kPair4) {
+                            ad[h][0] = byte_shl1<0>(v, six) | row4;
+                            ad[h][1] = byte_shl1<1>(v, six) | row4;
+                            ad[h][2] = byte_shl1<2>(v, six) | row4;
+                            ad[h][3] = byte_shl1<3>(v, six) | row4;
+                        } else {
+                            ad[h][0] = TT::template addr<0>(v, rowbase);
+                            ad[h][1] = TT::template addr<1>(v, rowbase);
+                            ad[h][2] = TT::template addr<2>(v, rowbase);
+                            ad[h][3] = TT::template addr<3>(v, rowbase);
+                        }
                     }
 #pragma unroll
                     for (int h = 0; h < 2; ++h)
@@ -251,7 +276,25 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
     // order).
     {
         const int srow = tid & 15, scopy = (tid >> 4) & 1, part = tid >> 5, nparts = nth >> 5;
-        if constexpr (TT::kPair) {
+        if constexpr (TT::kPair4) {
+            // the rows as stored (16 entries = 32 bytes each) first, then the 256 pair entries of every row:
+            // thread (row, part) writes entries part, part + nth / 16, ...: 16 rows x 2 parts = 32 banks a clock
+            for (int e = tid; e < R * kTileRows * 8; e += nth) {
+                const int r = e >> 3;
+                const int row = row0 + r < M ? row0 + r : M - 1;
+                reinterpret_cast<uint32_t *>(nat)[e] = reinterpret_cast<const uint32_t *>(lut + (size_t)row * 16)[e & 7];
+            }
+            issue(2 * p, true, XA, QA);
+            __syncthreads();
+            const int prow = tid & 15, ppart = tid >> 4, pparts = nth >> 4;
+#pragma unroll
+            for (int tile = 0; tile < R; ++tile) {
+                const uint16_t *src = nat + (tile * kTileRows + prow) * 16;
+                uint8_t *base = tab + tile * TT::kTileBytes + (prow << 2);
+                for (int d = ppart; d < 256; d += pparts)
+                    *reinterpret_cast<uint32_t *>(base + (d << 6)) = (uint32_t)src[pair4_even(d)] | ((uint32_t)src[pair4_odd(d)] << 16);
+            }
+        } else if constexpr (TT::kPair) {
             // natural rows (8 entries = 16 bytes each) first, then the pair entries from LDS
             for (int e = tid; e < R * kTileRows * 4; e += nth) {
                 const int r = e >> 2;
