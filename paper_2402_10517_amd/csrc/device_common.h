@@ -386,8 +386,8 @@ __device__ __forceinline__ void merge_words_pair4(const uint32_t (&q)[4], uint32
 }
 // Positions in the stored 4-bit table (slice 0, 1, 3, 2 at bits 3, 2, 1, 0) of the even and the odd slot of
 // pair index p.
-__device__ __forceinline__ int pair4_even(int p) { return ((p >> 3) & 8) | ((p >> 2) & 4) | ((p << 1) & 2) | ((p >> 2) & 1); }
-__device__ __forceinline__ int pair4_odd(int p) { return ((p >> 4) & 8) | ((p >> 3) & 4) | (p & 2) | ((p >> 3) & 1); }
+__device__ __forceinline__ constexpr int pair4_even(int p) { return ((p >> 3) & 8) | ((p >> 2) & 4) | ((p << 1) & 2) | ((p >> 2) & 1); }
+__device__ __forceinline__ constexpr int pair4_odd(int p) { return ((p >> 4) & 8) | ((p >> 3) & 4) | (p & 2) | ((p >> 3) & 1); }
 
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));

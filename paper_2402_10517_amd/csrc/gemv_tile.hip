@@ -40,10 +40,12 @@
 //     of 14 and 7, no clean-up), a row's 256 pair entries are built in LDS from its 16 stored
 //     centroids, one copy, entry p of row i at (p << 6) | (i << 2) (two operations per address, but
 //     per pair, and no pack before the matrix instruction); a row still owns its bank, the two lane
-//     groups of a clock collide only when their indices have the same parity.  Here that pays (28672 x
-//     8192 at batch 8: 49 -> 45 us, 8192 x 28672: 48 -> 42); in the batch-1 kernel, where all 64 lanes
-//     gather from one row's 256 dwords, the bank conflicts eat the gain.
+//     groups of a clock collide only when their indices have the same parity.  Here that pays (same box,
+//     alternating runs at batch 8: 28672 x 8192 46 -> 42 us, 8192 x 8192 16 -> 13.5, 8192 x 28672
+//     46 -> 41), once the table build is cheap (below); in the batch-1 kernel, where all 64 lanes gather
+//     from one row's 256 dwords, the bank conflicts eat the gain.
 // Requires K % 256 == 0 (an octet is entirely inside or outside a ragged last span) and batch <= 8.
+#include <type_traits>
 #include "device_common.h"
 #include "launchers.h"
 
@@ -86,7 +88,7 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
     constexpr int kTabBytes = R * TT::kTileBytes, kRedBytes = (MAXT / 64) * R * kTileRows * 16 * 4;
     __shared__ __attribute__((aligned(16))) uint8_t smem[kTabBytes > kRedBytes ? kTabBytes : kRedBytes];
     uint8_t *tab = smem;
-    __shared__ __attribute__((aligned(16))) uint16_t nat[TT::kPair ? R * kTileRows * 8 : TT::kPair4 ? R * kTileRows * 16 : 8]; // the rows as stored (pair paths)
+    __shared__ __attribute__((aligned(16))) uint16_t nat[TT::kPair ? R * kTileRows * 8 : TT::kPair4 ? R * kTileRows * 18 : 8]; // the rows as stored (pair paths)
     float(*red)[R][kTileRows][16] = reinterpret_cast<float(*)[R][kTileRows][16]>(smem);
 
     const int tid = threadIdx.x, nth = blockDim.x;
@@ -277,22 +279,45 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
     {
         const int srow = tid & 15, scopy = (tid >> 4) & 1, part = tid >> 5, nparts = nth >> 5;
         if constexpr (TT::kPair4) {
-            // the rows as stored (16 entries = 32 bytes each) first, then the 256 pair entries of every row:
-            // thread (row, part) writes entries part, part + nth / 16, ...: 16 rows x 2 parts = 32 banks a clock
+            // the rows as stored (16 entries = 32 bytes each; 36 bytes apart in LDS, so that the rows fall on
+            // different banks) first, then the 256 pair entries of every row: thread (row, part) writes entries
+            // part + k * parts, 16 rows x 2 parts = 32 banks a clock.  With 256 or 512 threads the loop over k
+            // is unrolled: the even and odd table positions are then the thread's own (from `part`) plus a
+            // constant, i.e. an immediate offset of the LDS read, and an entry costs two reads, one pack and one
+            // write.
+            constexpr int kNatDwords = 9;
             for (int e = tid; e < R * kTileRows * 8; e += nth) {
                 const int r = e >> 3;
                 const int row = row0 + r < M ? row0 + r : M - 1;
-                reinterpret_cast<uint32_t *>(nat)[e] = reinterpret_cast<const uint32_t *>(lut + (size_t)row * 16)[e & 7];
+                reinterpret_cast<uint32_t *>(nat)[r * kNatDwords + (e & 7)] = reinterpret_cast<const uint32_t *>(lut + (size_t)row * 16)[e & 7];
             }
             issue(2 * p, true, XA, QA);
             __syncthreads();
-            const int prow = tid & 15, ppart = tid >> 4, pparts = nth >> 4;
+            const int prow = tid & 15, ppart = tid >> 4;
+            auto build = [&](auto log2_parts) {
+                constexpr int L = decltype(log2_parts)::value;
+                const uint16_t *even = nat + prow * (2 * kNatDwords) + pair4_even(ppart);
+                const uint16_t *odd = nat + prow * (2 * kNatDwords) + pair4_odd(ppart);
+                uint8_t *base = tab + (prow << 2) + (ppart << 6);
 #pragma unroll
-            for (int tile = 0; tile < R; ++tile) {
-                const uint16_t *src = nat + (tile * kTileRows + prow) * 16;
-                uint8_t *base = tab + tile * TT::kTileBytes + (prow << 2);
-                for (int d = ppart; d < 256; d += pparts)
-                    *reinterpret_cast<uint32_t *>(base + (d << 6)) = (uint32_t)src[pair4_even(d)] | ((uint32_t)src[pair4_odd(d)] << 16);
+                for (int tile = 0; tile < R; ++tile)
+#pragma unroll
+                    for (int k = 0; k < (256 >> L); ++k)
+                        *reinterpret_cast<uint32_t *>(base + tile * TT::kTileBytes + (k << (L + 6))) =
+                            (uint32_t)even[tile * kTileRows * 2 * kNatDwords + pair4_even(k << L)] |
+                            ((uint32_t)odd[tile * kTileRows * 2 * kNatDwords + pair4_odd(k << L)] << 16);
+            };
+            if (nth == 256) build(std::integral_constant<int, 4>{});
+            else if (nth == 512) build(std::integral_constant<int, 5>{});
+            else {
+                const int pparts = nth >> 4;
+#pragma unroll
+                for (int tile = 0; tile < R; ++tile) {
+                    const uint16_t *src = nat + (tile * kTileRows + prow) * (2 * kNatDwords);
+                    uint8_t *base = tab + tile * TT::kTileBytes + (prow << 2);
+                    for (int d = ppart; d < 256; d += pparts)
+                        *reinterpret_cast<uint32_t *>(base + (d << 6)) = (uint32_t)src[pair4_even(d)] | ((uint32_t)src[pair4_odd(d)] << 16);
+                }
             }
         } else if constexpr (TT::kPair) {
             // natural rows (8 entries = 16 bytes each) first, then the pair entries from LDS
