@@ -96,11 +96,11 @@ template <int B> struct Table {
 // The 64-entry table of centroid pairs of the 3-bit path (Section 5.3 "Merging Table Lookups"): pair
 // index bit 2k is code bit k of the even slot, bit 2k+1 is code bit k of the odd slot.  Entry i6 of a
 // row = (centroid of the even slot's code, centroid of the odd slot's code), from the natural row.
+__device__ __forceinline__ constexpr int pair3_even(int i6) { return (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4); }
+__device__ __forceinline__ constexpr int pair3_odd(int i6) { return ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4); }
 __device__ __forceinline__ uint32_t pair_entry(const uint16_t *nat_row, int i6)
 {
-    const int even = (i6 & 1) | ((i6 >> 1) & 2) | ((i6 >> 2) & 4);
-    const int odd = ((i6 >> 1) & 1) | ((i6 >> 2) & 2) | ((i6 >> 3) & 4);
-    return (uint32_t)nat_row[even] | ((uint32_t)nat_row[odd] << 16);
+    return (uint32_t)nat_row[pair3_even(i6)] | ((uint32_t)nat_row[pair3_odd(i6)] << 16);
 }
 
 template <int ctrl> __device__ __forceinline__ float dpp_get(float v)

@@ -88,7 +88,7 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
     constexpr int kTabBytes = R * TT::kTileBytes, kRedBytes = (MAXT / 64) * R * kTileRows * 16 * 4;
     __shared__ __attribute__((aligned(16))) uint8_t smem[kTabBytes > kRedBytes ? kTabBytes : kRedBytes];
     uint8_t *tab = smem;
-    __shared__ __attribute__((aligned(16))) uint16_t nat[TT::kPair ? R * kTileRows * 8 : TT::kPair4 ? R * kTileRows * 18 : 8]; // the rows as stored (pair paths)
+    __shared__ __attribute__((aligned(16))) uint16_t nat[TT::kPair ? R * kTileRows * 10 : TT::kPair4 ? R * kTileRows * 18 : 8]; // the rows as stored (pair paths)
     float(*red)[R][kTileRows][16] = reinterpret_cast<float(*)[R][kTileRows][16]>(smem);
 
     const int tid = threadIdx.x, nth = blockDim.x;
@@ -320,19 +320,40 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
                 }
             }
         } else if constexpr (TT::kPair) {
-            // natural rows (8 entries = 16 bytes each) first, then the pair entries from LDS
+            // natural rows (8 entries = 16 bytes each, 20 bytes apart in LDS: 16 rows on 16 banks) first, then the
+            // pair entries from LDS; unrolled like the 4-bit build above (entries part + k * parts of a thread's
+            // row and copy: the even and odd centroid of an entry sit at the thread's own offset + a constant)
+            constexpr int kNatDwords = 5;
             for (int e = tid; e < R * kTileRows * 4; e += nth) {
                 const int r = e >> 2;
                 const int row = row0 + r < M ? row0 + r : M - 1;
-                reinterpret_cast<uint32_t *>(nat)[e] = reinterpret_cast<const uint32_t *>(lut + (size_t)row * 8)[e & 3];
+                reinterpret_cast<uint32_t *>(nat)[r * kNatDwords + (e & 3)] = reinterpret_cast<const uint32_t *>(lut + (size_t)row * 8)[e & 3];
             }
             issue(2 * p, true, XA, QA);
             __syncthreads();
+            auto build = [&](auto log2_parts) {
+                constexpr int L = decltype(log2_parts)::value;
+                const uint16_t *even = nat + srow * (2 * kNatDwords) + pair3_even(part);
+                const uint16_t *odd = nat + srow * (2 * kNatDwords) + pair3_odd(part);
+                uint8_t *base = tab + ((srow << 2) | (scopy << 6)) + (TT::byte_of(part) << TT::kShift);
 #pragma unroll
-            for (int tile = 0; tile < R; ++tile) {
-                uint8_t *base = tab + tile * TT::kTileBytes + ((srow << 2) | (scopy << 6));
-                for (int d = part; d < 64; d += nparts)
-                    *reinterpret_cast<uint32_t *>(base + (TT::byte_of(d) << TT::kShift)) = pair_entry(nat + (tile * kTileRows + srow) * 8, d);
+                for (int tile = 0; tile < R; ++tile)
+#pragma unroll
+                    for (int k = 0; k < (64 >> L); ++k)
+                        *reinterpret_cast<uint32_t *>(base + tile * TT::kTileBytes + (TT::byte_of(k << L) << TT::kShift)) =
+                            (uint32_t)even[tile * kTileRows * 2 * kNatDwords + pair3_even(k << L)] |
+                            ((uint32_t)odd[tile * kTileRows * 2 * kNatDwords + pair3_odd(k << L)] << 16);
+            };
+            if (nth == 256) build(std::integral_constant<int, 3>{});
+            else if (nth == 512) build(std::integral_constant<int, 4>{});
+            else {
+#pragma unroll
+                for (int tile = 0; tile < R; ++tile) {
+                    uint8_t *base = tab + tile * TT::kTileBytes + ((srow << 2) | (scopy << 6));
+                    for (int d = part; d < 64; d += nparts)
+                        *reinterpret_cast<uint32_t *>(base + (TT::byte_of(d) << TT::kShift)) =
+                            pair_entry(nat + (tile * kTileRows + srow) * (2 * kNatDwords), d);
+                }
             }
         } else {
             constexpr int kPieces = (2 << B) / 16; // 16-byte pieces (8 entries) of a row's table
