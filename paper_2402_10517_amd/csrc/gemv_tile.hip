@@ -475,8 +475,11 @@ template <int B, int R> static hipError_t launch_tile_r(const GemvArgs &a, hipSt
 template <int B> static hipError_t launch_tile_b(const GemvArgs &a, hipStream_t stream)
 {
     // two tiles per workgroup re-read and re-arrange the activations half as often, at more registers:
-    // measured faster on rows of 16384 columns or more only
-    const int r = a.variant == 9 ? 1 : a.variant == 10 ? 2 : a.K >= 16384 ? 2 : 1;
+    // measured faster on rows of 16384 columns or more, and at 3 bits (where the loads outweigh the
+    // arithmetic) on matrices tall enough to fill the device with half as many workgroups (28672 x 8192 at
+    // batch 4 and 8: 29-34 -> 28 us; 8192 x 8192: 11.8 -> 12.5, so not there)
+    const int tiles = (a.M + 15) / 16;
+    const int r = a.variant == 9 ? 1 : a.variant == 10 ? 2 : (a.K >= 16384 || (B == 3 && tiles >= 1536)) ? 2 : 1;
     if (r == 2) return launch_tile_r<B, 2>(a, stream);
     return launch_tile_r<B, 1>(a, stream);
 }
