@@ -232,9 +232,11 @@ def test_matrix_core_variant_with_in_block_exchange(B, batch):
 def test_matrix_core_variant_on_tiles_of_16_rows(B, batch):
     # forced for every b and batch >= 2: one octet of chunks, several spans with a ragged last span, an
     # odd number of octets, more octet pairs than waves, rows not a multiple of 4 or 16 (tiles and row
-    # groups partly or wholly past the matrix), one and two tiles per workgroup
+    # groups partly or wholly past the matrix), one and two tiles per workgroup; workgroups of 1, 2, 3, 4 and 8
+    # waves (the pair tables of the 3- and 4-bit paths are built by a different loop at 4 and 8 waves)
     for variant in (B.VARIANT_TILE, B.VARIANT_TILE2):
-        for (M, K) in [(37, 256), (70, 2048 + 768), (21, 3 * 2048 + 256), (9, 9 * 2048 + 512), (130, 4096), (16, 512)]:
+        for (M, K) in [(37, 256), (70, 2048 + 768), (21, 3 * 2048 + 256), (9, 9 * 2048 + 512), (130, 4096), (16, 512),
+                       (20, 768), (40, 1280)]:
             idx, luts, x = inputs.make_case(27, M, K, batch=batch, sigma=0.01)
             pm = B.ap_pack(idx, luts).set_options(variant=variant)
             for b in ALL_BITS:
