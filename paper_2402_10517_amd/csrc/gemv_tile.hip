@@ -38,11 +38,10 @@
 //     per dword.  The 4-bit path looks pairs up as well: slice 3 is rotated to rotation 0 so that a
 //     merged byte is the 8-bit index of a column pair (8 selects and 4 rotates per 32 weights instead
 //     of 14 and 7, no clean-up), a row's 256 pair entries are built in LDS from its 16 stored
-//     centroids, one copy, entry p of row i at (p << 6) | (i << 2) (two operations per address, but
-//     per pair, and no pack before the matrix instruction); a row still owns its bank, the two lane
-//     groups of a clock collide only when their indices have the same parity.  Here that pays (same box,
-//     alternating runs at batch 8: 28672 x 8192 46 -> 42 us, 8192 x 8192 16 -> 13.5, 8192 x 28672
-//     46 -> 41), once the table build is cheap (below); in the batch-1 kernel, where all 64 lanes gather
+//     centroids, two copies, entry p of row i at (p << 7) | (c << 6) | (i << 2) (two operations per
+//     address, but per pair, and no pack before the matrix instruction).  Here that pays (same box,
+//     alternating runs at batch 8: 28672 x 8192 46 -> 39 us, 8192 x 8192 16 -> 13.5, 8192 x 28672
+//     46 -> 36), once the table build is cheap (below); in the batch-1 kernel, where all 64 lanes gather
 //     from one row's 256 dwords, the bank conflicts eat the gain.
 // Requires K % 256 == 0 (an octet is entirely inside or outside a ragged last span) and batch <= 8.
 #include <type_traits>
@@ -53,8 +52,8 @@ namespace apgemv {
 
 template <int B> struct TileTable {
     static constexpr bool kPair = (B == 3);
-    // 4 bits: a 256-entry table of centroid pairs per row, one copy, entry p of row i at (p << 6) | (i << 2)
-    // (the two lane groups of a clock meet in a bank when their pair indices have the same parity)
+    // 4 bits: a 256-entry table of centroid pairs per row, two copies like the other tables: entry p of row i
+    // for lane groups of parity c at (p << 7) | (c << 6) | (i << 2)
     static constexpr bool kPair4 = (B == 4);
     static constexpr uint32_t kMask = kPair ? 0xFCu : Table<B>::addr_mask(); // index bits inside a merged byte
     static constexpr int kLow = (kMask & 1) ? 0 : (kMask & 2) ? 1 : 2;       // lowest of them
@@ -62,7 +61,7 @@ template <int B> struct TileTable {
     static constexpr int kExtra = kPerm ? kLow : 0;                          // extra rotation of the index words
     static constexpr uint32_t kClean = (kMask >> kExtra) * 0x01010101u;      // index bits of the rotated words
     static constexpr int kShift = kPerm ? 8 : 7 - kLow;                      // entry value -> address
-    static constexpr int kTileBytes = kPair4 ? 256 * 64 : (int)((kMask >> kLow) + 1) << (kPerm ? 8 : 7); // 16 rows x 2 copies x 4 bytes per entry (x 2 unused)
+    static constexpr int kTileBytes = kPair4 ? 256 * 128 : (int)((kMask >> kLow) + 1) << (kPerm ? 8 : 7); // 16 rows x 2 copies x 4 bytes per entry (x 2 unused)
     // value in a (rotated) index byte of the entry stored at position p of a row (lut_stored_pos order; pair index for B = 3)
     __device__ static constexpr uint32_t byte_of(uint32_t p)
     {
@@ -136,9 +135,8 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
                                                    : 0x80000000u;
     const int xperm_src = (((i & 7) << 3) | ((i >> 3) << 2) | (kg ^ (((i >> 2) & 1) << 1))) << 2; // byte address of the source lane
     const uint32_t rowbase = ((uint32_t)i << 2) | ((uint32_t)(kg & 1) << 6);
-    const uint32_t row4 = (uint32_t)i << 2; // pair path at 4 bits: one copy
-    uint32_t six = 6;                       // its shift amount, kept in a register (SDWA operand)
-    asm("" : "+v"(six));
+    uint32_t seven = 7; // shift amount of the 4-bit pair path's addresses, kept in a register (SDWA operand)
+    asm("" : "+v"(seven));
 
     float4_t acc[R][2]; // one accumulator per quad of an octet: independent chains of matrix instructions
 #pragma unroll
@@ -209,10 +207,10 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
                     for (int h = 0; h < 2; ++h) {
                         const uint32_t v = W[h][2 * t];
                         if constexpr (TT::kPair4) {
-                            ad[h][0] = byte_shl1<0>(v, six) | row4;
-                            ad[h][1] = byte_shl1<1>(v, six) | row4;
-                            ad[h][2] = byte_shl1<2>(v, six) | row4;
-                            ad[h][3] = byte_shl1<3>(v, six) | row4;
+                            ad[h][0] = byte_shl1<0>(v, seven) | rowbase;
+                            ad[h][1] = byte_shl1<1>(v, seven) | rowbase;
+                            ad[h][2] = byte_shl1<2>(v, seven) | rowbase;
+                            ad[h][3] = byte_shl1<3>(v, seven) | rowbase;
                         } else {
                             ad[h][0] = TT::template addr<0>(v, rowbase);
                             ad[h][1] = TT::template addr<1>(v, rowbase);
@@ -280,8 +278,8 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
         const int srow = tid & 15, scopy = (tid >> 4) & 1, part = tid >> 5, nparts = nth >> 5;
         if constexpr (TT::kPair4) {
             // the rows as stored (16 entries = 32 bytes each; 36 bytes apart in LDS, so that the rows fall on
-            // different banks) first, then the 256 pair entries of every row: thread (row, part) writes entries
-            // part + k * parts, 16 rows x 2 parts = 32 banks a clock.  With 256 or 512 threads the loop over k
+            // different banks) first, then the 256 pair entries of every row and copy: thread (row, copy, part) writes
+            // entries part + k * parts, 16 rows x 2 copies = 32 banks a clock.  With 256 or 512 threads the loop over k
             // is unrolled: the even and odd table positions are then the thread's own (from `part`) plus a
             // constant, i.e. an immediate offset of the LDS read, and an entry costs two reads, one pack and one
             // write.
@@ -293,30 +291,28 @@ __device__ __forceinline__ void gemv_tile_body(const uint8_t *__restrict__ slice
             }
             issue(2 * p, true, XA, QA);
             __syncthreads();
-            const int prow = tid & 15, ppart = tid >> 4;
             auto build = [&](auto log2_parts) {
                 constexpr int L = decltype(log2_parts)::value;
-                const uint16_t *even = nat + prow * (2 * kNatDwords) + pair4_even(ppart);
-                const uint16_t *odd = nat + prow * (2 * kNatDwords) + pair4_odd(ppart);
-                uint8_t *base = tab + (prow << 2) + (ppart << 6);
+                const uint16_t *even = nat + srow * (2 * kNatDwords) + pair4_even(part);
+                const uint16_t *odd = nat + srow * (2 * kNatDwords) + pair4_odd(part);
+                uint8_t *base = tab + ((srow << 2) | (scopy << 6)) + (part << 7);
 #pragma unroll
                 for (int tile = 0; tile < R; ++tile)
 #pragma unroll
                     for (int k = 0; k < (256 >> L); ++k)
-                        *reinterpret_cast<uint32_t *>(base + tile * TT::kTileBytes + (k << (L + 6))) =
+                        *reinterpret_cast<uint32_t *>(base + tile * TT::kTileBytes + (k << (L + 7))) =
                             (uint32_t)even[tile * kTileRows * 2 * kNatDwords + pair4_even(k << L)] |
                             ((uint32_t)odd[tile * kTileRows * 2 * kNatDwords + pair4_odd(k << L)] << 16);
             };
-            if (nth == 256) build(std::integral_constant<int, 4>{});
-            else if (nth == 512) build(std::integral_constant<int, 5>{});
+            if (nth == 256) build(std::integral_constant<int, 3>{});
+            else if (nth == 512) build(std::integral_constant<int, 4>{});
             else {
-                const int pparts = nth >> 4;
 #pragma unroll
                 for (int tile = 0; tile < R; ++tile) {
-                    const uint16_t *src = nat + (tile * kTileRows + prow) * (2 * kNatDwords);
-                    uint8_t *base = tab + tile * TT::kTileBytes + (prow << 2);
-                    for (int d = ppart; d < 256; d += pparts)
-                        *reinterpret_cast<uint32_t *>(base + (d << 6)) = (uint32_t)src[pair4_even(d)] | ((uint32_t)src[pair4_odd(d)] << 16);
+                    const uint16_t *src = nat + (tile * kTileRows + srow) * (2 * kNatDwords);
+                    uint8_t *base = tab + tile * TT::kTileBytes + ((srow << 2) | (scopy << 6));
+                    for (int d = part; d < 256; d += nparts)
+                        *reinterpret_cast<uint32_t *>(base + (d << 7)) = (uint32_t)src[pair4_even(d)] | ((uint32_t)src[pair4_odd(d)] << 16);
                 }
             }
         } else if constexpr (TT::kPair) {
