@@ -60,6 +60,37 @@ def timed_launches(torch, fn, reps, samples=3):
     return sorted(out)[len(out) // 2]
 
 
+def probe_issue(torch, B, sp):
+    """Issue rates of the instruction kinds the dequantising kernels consist of (ap_probe_issue): 2048 workgroups
+    of 256 threads = 32 waves per CU, 8 per SIMD; every wave runs `passes` passes of one group of instructions."""
+    kinds = [(0, "8 ds_read_b32, own bank per lane", 8, 0), (1, "8 ds_read_b32, 2-way bank conflict", 8, 0),
+             (2, "8 ds_bpermute_b32", 8, 0), (3, "4 ds_read_b128", 4, 0), (4, "32 v_perm_b32", 0, 32),
+             (5, "8 ds_read_b32 + 32 v_perm_b32", 8, 32), (6, "8 ds_bpermute_b32 + 32 v_perm_b32", 8, 32)]
+    passes, waves_per_cu, waves_per_simd = 2000, 2048 * 4 / 256, 2048 * 4 / 1024
+    rows = []
+    for kind, what, n_lds, n_valu in kinds:
+        def launch(_r, kind=kind):
+            if B.lib.ap_probe_issue(kind, passes, sp) != 0:
+                raise RuntimeError("ap_probe_issue failed")
+        if B.lib.ap_probe_issue(kind, 10, sp) != 0:
+            raise RuntimeError("ap_probe_issue failed")
+        torch.cuda.synchronize()
+        us = timed_launches(torch, launch, 3)
+        row = dict(kind=kind, group=what, us=round(us, 1))
+        if n_lds:
+            row["ns_per_lds_instruction_per_cu"] = round(us * 1e3 / (waves_per_cu * passes * n_lds), 3)
+        if n_valu:
+            row["ns_per_valu_instruction_per_simd"] = round(us * 1e3 / (waves_per_simd * passes * n_valu), 3)
+        rows.append(row)
+        print("  kind %d  %-36s %8.1f us%s%s" % (
+            kind, what, us,
+            "  %6.2f ns per LDS instruction and CU" % row["ns_per_lds_instruction_per_cu"] if n_lds else "",
+            "  %6.2f ns per VALU instruction and SIMD" % row["ns_per_valu_instruction_per_simd"] if n_valu else ""),
+            file=sys.stderr)
+    print(json.dumps(dict(metric="issue rates of LDS and VALU instruction groups (2048 workgroups x 256 threads, %d passes)"
+                          % passes, unit="us", n_gpus=1, rows=rows)))
+
+
 def large_batch(args, np, torch, B, inputs, dev):
     """Dequantise kernel (HBM-bound: reads b/8 bytes, writes 2 bytes per weight) and the
     dequantise + rocBLAS FP16 GEMM path, on the Llama-2-7B shapes."""
@@ -292,6 +323,9 @@ def main():
                          "path (batch 16..512) on the headline shapes; prints one JSON line")
     ap.add_argument("--decode-step", action="store_true",
                     help="instead of the headline line: the 7B-shaped decode step in every issue mode; one JSON line")
+    ap.add_argument("--probe-issue", action="store_true",
+                    help="instead of the headline line: issue rates of the LDS and VALU instructions the kernels "
+                         "are made of (ap_probe_issue); one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -311,6 +345,9 @@ def main():
     bits = list(range(3, 9))
     stream = torch.cuda.current_stream()
     sp = ctypes.c_void_p(stream.cuda_stream)
+    if args.probe_issue:
+        probe_issue(torch, B, sp)
+        return
     if args.decode_step:
         res, seq = decode_step_rows(np, torch, B, inputs, dev, ["separate", "fused", "layer_list", "list32"],
                                     64 if args.batch == 1 else 18, batch=args.batch)

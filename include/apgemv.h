@@ -278,6 +278,23 @@ ap_status ap_quantize(const float *w, const float *sens, int M, int K, int n_see
  */
 ap_status ap_probe_read(const void *dev_buf, size_t bytes, void *stream);
 
+/*
+ * Measurement aid, not part of the method: launches 2048 workgroups of 256 threads (8 resident waves
+ * per SIMD) in which every wave runs `passes` (1 .. 2^20) passes of one fixed group of independent
+ * instructions, so that the time of the launch divided by the instructions per compute unit is the
+ * issue rate of that kind on this device.  The kinds are the instructions the dequantising kernels are
+ * made of; the ceilings they set (an LDS read costs a SIMD about as much issue time as a vector
+ * instruction, and the two overlap only partly) are what bounds those kernels before HBM does.
+ *   kind 0  8 ds_read_b32, every lane its own bank     kind 1  8 ds_read_b32 with 2-way bank conflicts
+ *   kind 2  8 ds_bpermute_b32                          kind 3  4 ds_read_b128
+ *   kind 4  32 v_perm_b32                              kind 5  kind 0 and kind 4 together
+ *   kind 6  kind 2 and kind 4 together
+ * Uses no device memory beyond its own LDS; asynchronous on `stream`; AP_ERR_INVALID_ARG for another
+ * kind or pass count.
+ */
+#define AP_PROBE_ISSUE_KINDS 7
+ap_status ap_probe_issue(int kind, int passes, void *stream);
+
 /* Shape and supported bit-widths of a handle; any output pointer may be NULL. */
 ap_status ap_matrix_info(const ap_matrix *h, int *M, int *K, int *n, unsigned *lut_mask);
 

@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "AP_OK", 1: "AP_ERR_INVALID_ARG", 2: "AP_ERR_SHAPE", 3: "AP_E
 
 EXPORTS = ["ap_packed_size", "ap_pack_host", "ap_unpack_host", "ap_blob_lut_entry",
            "ap_read_extent", "ap_pack", "ap_attach", "ap_set_option", "ap_unpack", "ap_gemv", "ap_gemv_multi", "ap_gemv_list", "ap_gemv_list_batch", "ap_dequantize",
-           "ap_gemm_workspace_size", "ap_gemm", "ap_gemm_static", "ap_quantize", "ap_probe_read", "ap_matrix_info",
+           "ap_gemm_workspace_size", "ap_gemm", "ap_gemm_static", "ap_quantize", "ap_probe_read", "ap_probe_issue", "ap_matrix_info",
            "ap_free", "ap_strerror"]
 
 
@@ -65,6 +65,7 @@ def _load():
     L.ap_gemm_static.argtypes = [vp, ci, vp, vp, ci, vp]
     L.ap_quantize.argtypes = [vp, vp, ci, ci, ci, ci, ci, vp, vp]
     L.ap_probe_read.argtypes = [vp, sz, vp]
+    L.ap_probe_issue.argtypes = [ctypes.c_int, ctypes.c_int, vp]
     L.ap_matrix_info.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci),
                                  ctypes.POINTER(cu)]
     L.ap_free.argtypes = [vp]

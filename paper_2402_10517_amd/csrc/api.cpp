@@ -409,6 +409,12 @@ extern "C" ap_status ap_probe_read(const void *dev_buf, size_t bytes, void *stre
                                                                                               : AP_ERR_HIP;
 }
 
+extern "C" ap_status ap_probe_issue(int kind, int passes, void *stream)
+{
+    if (kind < 0 || kind >= AP_PROBE_ISSUE_KINDS || passes < 1 || passes > (1 << 20)) return AP_ERR_INVALID_ARG;
+    return launch_probe_issue(kind, passes, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
 extern "C" ap_status ap_matrix_info(const ap_matrix *h, int *M, int *K, int *n, unsigned *lut_mask)
 {
     if (!handle_ok(h)) return AP_ERR_INVALID_ARG;

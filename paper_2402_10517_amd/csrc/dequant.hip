@@ -132,4 +132,75 @@ hipError_t launch_probe_read(const void *dev_buf, size_t bytes, hipStream_t stre
     return hipGetLastError();
 }
 
+// Issue rates of the instruction kinds the dequantising kernels are made of (a measurement aid: the
+// GEMV kernels are bound by the issue of these instructions before they are bound by HBM).  Every wave
+// runs `passes` passes of one fixed group of independent instructions and waits for the group's LDS
+// results at the end of a pass; 2048 workgroups of 256 threads, i.e. 8 resident waves per SIMD.
+//   0: 8 ds_read_b32, every lane its own bank      1: 8 ds_read_b32, two lanes per bank (2-way conflict)
+//   2: 8 ds_bpermute_b32                           3: 4 ds_read_b128
+//   4: 32 v_perm_b32                               5: kind 0 + kind 4      6: kind 2 + kind 4
+template <int KIND> __global__ __launch_bounds__(256) void probe_issue_kernel(uint32_t *sink, int passes)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t mem[4096];
+    for (int k = threadIdx.x; k < 4096; k += blockDim.x) mem[k] = (uint32_t)k * 2654435761u;
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63;
+    // byte address of the lane's word: consecutive dwords, every second dword (KIND 1), or 16-byte slots
+    const uint32_t addr = KIND == 1 ? (lane * 2 & 127) * 4 + (lane >> 6) : KIND == 3 ? lane * 16 : lane * 4;
+    uint32_t acc = 0, t0 = lane, t1 = lane ^ 5, t2 = lane + 7, t3 = ~lane;
+    for (int it = 0; it < passes; ++it) {
+        uint32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0, a4 = 0, a5 = 0, a6 = 0, a7 = 0;
+        if constexpr (KIND == 0 || KIND == 1 || KIND == 5)
+            asm volatile("ds_read_b32 %0, %8\n ds_read_b32 %1, %8 offset:1024\n ds_read_b32 %2, %8 offset:2048\n"
+                         "ds_read_b32 %3, %8 offset:3072\n ds_read_b32 %4, %8 offset:4096\n ds_read_b32 %5, %8 offset:5120\n"
+                         "ds_read_b32 %6, %8 offset:6144\n ds_read_b32 %7, %8 offset:7168"
+                         : "=&v"(a0), "=&v"(a1), "=&v"(a2), "=&v"(a3), "=&v"(a4), "=&v"(a5), "=&v"(a6), "=&v"(a7)
+                         : "v"(addr));
+        if constexpr (KIND == 2 || KIND == 6)
+            asm volatile("ds_bpermute_b32 %0, %8, %9\n ds_bpermute_b32 %1, %8, %9\n ds_bpermute_b32 %2, %8, %9\n"
+                         "ds_bpermute_b32 %3, %8, %9\n ds_bpermute_b32 %4, %8, %9\n ds_bpermute_b32 %5, %8, %9\n"
+                         "ds_bpermute_b32 %6, %8, %9\n ds_bpermute_b32 %7, %8, %9"
+                         : "=&v"(a0), "=&v"(a1), "=&v"(a2), "=&v"(a3), "=&v"(a4), "=&v"(a5), "=&v"(a6), "=&v"(a7)
+                         : "v"(addr), "v"(acc));
+        if constexpr (KIND == 3) {
+            u32x4 b0, b1, b2, b3;
+            asm volatile("ds_read_b128 %0, %4\n ds_read_b128 %1, %4 offset:4096\n ds_read_b128 %2, %4 offset:8192\n"
+                         "ds_read_b128 %3, %4 offset:12288"
+                         : "=&v"(b0), "=&v"(b1), "=&v"(b2), "=&v"(b3)
+                         : "v"(addr));
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            a0 = b0[0] ^ b1[1] ^ b2[2] ^ b3[3];
+        }
+        if constexpr (KIND >= 4) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+                asm volatile("v_perm_b32 %0, %0, %1, %4\n v_perm_b32 %1, %1, %2, %4\n v_perm_b32 %2, %2, %3, %4\n"
+                             "v_perm_b32 %3, %3, %0, %4"
+                             : "+v"(t0), "+v"(t1), "+v"(t2), "+v"(t3)
+                             : "v"(0x07020500u));
+        }
+        if constexpr (KIND != 3 && KIND != 4) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        acc ^= a0 ^ a1 ^ a2 ^ a3 ^ a4 ^ a5 ^ a6 ^ a7;
+    }
+    acc ^= t0 ^ t1 ^ t2 ^ t3;
+    if (acc == 0x9e3779b9u && sink) *sink = acc; // keeps the work alive; sink is null in practice
+}
+
+hipError_t launch_probe_issue(int kind, int passes, hipStream_t stream)
+{
+    const dim3 grid(2048), block(256);
+    uint32_t *none = nullptr;
+    switch (kind) {
+    case 0: hipLaunchKernelGGL(probe_issue_kernel<0>, grid, block, 0, stream, none, passes); break;
+    case 1: hipLaunchKernelGGL(probe_issue_kernel<1>, grid, block, 0, stream, none, passes); break;
+    case 2: hipLaunchKernelGGL(probe_issue_kernel<2>, grid, block, 0, stream, none, passes); break;
+    case 3: hipLaunchKernelGGL(probe_issue_kernel<3>, grid, block, 0, stream, none, passes); break;
+    case 4: hipLaunchKernelGGL(probe_issue_kernel<4>, grid, block, 0, stream, none, passes); break;
+    case 5: hipLaunchKernelGGL(probe_issue_kernel<5>, grid, block, 0, stream, none, passes); break;
+    case 6: hipLaunchKernelGGL(probe_issue_kernel<6>, grid, block, 0, stream, none, passes); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 } // namespace apgemv

@@ -65,6 +65,7 @@ hipError_t launch_matrix_tile_multi(const MultiArgs &a, int b, hipStream_t strea
 hipError_t launch_matrix_tile_list(ListArgs &a, int b, int batch, hipStream_t stream);
 hipError_t launch_dequantize(const GemvArgs &a, hipStream_t stream);
 hipError_t launch_probe_read(const void *dev_buf, size_t bytes, hipStream_t stream);
+hipError_t launch_probe_issue(int kind, int passes, hipStream_t stream);
 // Looks up, once per device, the device address of the static array ap_gemm_static writes the dense
 // weights to (the current device's copy); called where a matrix is set up on a device.
 bool static_scratch_setup();

@@ -28,6 +28,7 @@ hipError_t launch_matrix_tile_list(ListArgs &, int, int, hipStream_t) { return h
 hipError_t launch_gemv_list(ListArgs &, hipStream_t) { return hipErrorInvalidValue; }
 hipError_t launch_dequantize(const GemvArgs &, hipStream_t) { return hipErrorInvalidValue; }
 hipError_t launch_probe_read(const void *, size_t, hipStream_t) { return hipErrorInvalidValue; }
+hipError_t launch_probe_issue(int, int, hipStream_t) { return hipErrorInvalidValue; }
 bool static_scratch_setup() { return false; }
 bool dense_gemm_f16(const void *, const void *, void *, int, int, int, hipStream_t) { return false; }
 } // namespace apgemv

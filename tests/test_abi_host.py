@@ -179,6 +179,8 @@ def test_error_paths_before_any_device_work():
     assert L.ap_gemm(None, 4, fake_dev, fake_dev, 32, fake_dev, 1 << 20, None) == 1
     assert L.ap_probe_read(fake_dev, 1000, None) == 1                         # not a multiple of 16384
     assert L.ap_probe_read(None, 16384, None) == 1
+    assert L.ap_probe_issue(-1, 10, None) == 1 and L.ap_probe_issue(7, 10, None) == 1   # kinds are 0..6
+    assert L.ap_probe_issue(0, 0, None) == 1 and L.ap_probe_issue(0, (1 << 20) + 1, None) == 1
     assert L.ap_gemv(None, 4, fake_dev, fake_dev, 1, None) == 1
     assert L.ap_unpack(None, idx.ctypes.data, None) == 1
     assert L.ap_matrix_info(None, None, None, None, None) == 1

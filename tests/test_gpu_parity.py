@@ -597,3 +597,12 @@ def test_random_shapes_bit_widths_and_batches(B, seed):
             check_against_oracle(y, idx, luts[b], b, x)
         assert np.array_equal(B.ap_unpack(pm), idx)
         pm.close()
+
+
+def test_issue_probe_runs_every_kind(B):
+    """The measurement aid launches and completes for every kind (it has no output to compare)."""
+    import torch
+    for kind in range(7):
+        assert B.lib.ap_probe_issue(kind, 3, None) == 0
+    torch.cuda.synchronize()
+
