@@ -479,7 +479,12 @@ def main():
         call18(r)
     torch.cuda.synchronize()
     list_us = timed_launches(torch, call18, 5 * COPIES)
-    list_launches = len({min(8, (cs["K"] + 2047) // 2048) for cs in cases})
+    # one launch per class of waves per row group (one wave per span of 2048 columns up to 4 spans, half as many
+    # for 5 to 8 spans, 8 beyond)
+    def list_waves(K):
+        n = (K + 2047) // 2048
+        return (n + 1) // 2 if 5 <= n <= 8 else min(8, n)
+    list_launches = len({list_waves(cs["K"]) for cs in cases})
     list_call = dict(products=len(bits) * len(cases), launches=list_launches, us=round(list_us, 3), bytes=step_bytes,
                      GBps=round(step_bytes / list_us / 1e3, 1), frac_of_peak=round(step_bytes / list_us / 1e3 / HBM_PEAK_GBPS, 4))
     per_call = per_call_rows(torch, B, inputs, dev, 2, [1], bits, sp, args.variant, args.detail, warm=True)

@@ -17,6 +17,21 @@
 
 namespace apgemv {
 
+// Waves per group of 4 rows at batch 1 for a row of `nspans` spans of 2048 columns: one per span up to 4 spans
+// and 8 from 9 spans on, but rows of 5 to 8 spans take half as many waves, two spans each.  Measured, us per
+// single call, one wave per span -> half: 4096 x 11008 (6 spans) b = 3 7.2 -> 6.9, b = 5 10.7 -> 9.3, b = 6
+// 11.8 -> 10.1, b = 7 12.0 -> 11.2, level at b = 4 and 8; 5120 x 13824 (7 spans) b = 5 14.8 -> 12.4, b = 6
+// 16.2 -> 14.0, b = 7 18.0 -> 16.1, b = 8 19.9 -> 18.4, level at b = 3, 4; the headline list of 18 products
+// gains 10 % (same box, alternating runs).  The last wave of such a row is mostly empty, and set-up, barrier
+// and reduction are shared by fewer waves.  Not so on shorter rows (4 spans as 2 waves: level on 8192 x 8192 and
+// 28672 x 8192, 30 % slower on 1024 x 8192; 3 spans as 2 waves: 15 % slower) nor on 14 spans (7, 5 or 4 waves:
+// level).  Single calls and work lists use the same rule, so their outputs stay bit-identical.
+static inline int batch1_waves(int nspans)
+{
+    if (nspans >= 5 && nspans <= 8) return (nspans + 1) / 2;
+    return nspans < 8 ? nspans : 8;
+}
+
 // One workgroup per group of 4 rows; its waves stride over the row's spans of 2048 columns.
 // The table loads go out first, then the wave's first slice loads, then the tables are written to
 // LDS while the slice loads are still in flight; later
@@ -270,7 +285,7 @@ static hipError_t launch_list_class(const ListArgs &a, int nw, hipStream_t strea
     int total = 0, b = -1, max_nw = 1;
     for (int i = 0; i < a.count; ++i) {
         const int spans = (a.item[i].K / kChunkSlots + kSpanLanes - 1) / kSpanLanes;
-        const int w = spans < kMaxWaves ? spans : kMaxWaves;
+        const int w = batch1_waves(spans);
         if (w != nw) continue;
         sub.item[sub.count] = a.item[i];
         sub.group_begin[sub.count] = total;
@@ -302,7 +317,7 @@ hipError_t launch_gemv_list(ListArgs &a, hipStream_t stream)
     bool seen[9] = {};
     for (int i = 0; i < a.count; ++i) {
         const int spans = (a.item[i].K / kChunkSlots + kSpanLanes - 1) / kSpanLanes;
-        const int w = spans < 8 ? spans : 8;
+        const int w = batch1_waves(spans);
         if (seen[w]) continue;
         seen[w] = true;
         const hipError_t e = launch_list_class(a, w, stream);
@@ -444,6 +459,7 @@ static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
     int nw = kMaxWaves;
     if (a.waves_per_group > 0 && a.waves_per_group < nw) nw = a.waves_per_group;
     if (nw > nspans) nw = nspans;
+    if (NB == 1 && a.waves_per_group == 0) nw = batch1_waves(nspans);
     // several row groups per workgroup at batch 5..8 when every span has its own wave and there are
     // enough groups to keep the device full (at batch 2..4 the plain kernel measured faster)
     int rg = a.row_groups_per_wg;
