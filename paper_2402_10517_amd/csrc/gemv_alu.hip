@@ -17,7 +17,7 @@
 
 namespace apgemv {
 
-// Waves per group of 4 rows at batch 1 for a row of `nspans` spans of 2048 columns: one per span up to 4 spans
+// Waves per group of 4 rows at batch 1 and 2 for a row of `nspans` spans of 2048 columns: one per span up to 4 spans
 // and 8 from 9 spans on, but rows of 5 to 8 spans take half as many waves, two spans each.  Measured, us per
 // single call, one wave per span -> half: 4096 x 11008 (6 spans) b = 3 7.2 -> 6.9, b = 5 10.7 -> 9.3, b = 6
 // 11.8 -> 10.1, b = 7 12.0 -> 11.2, level at b = 4 and 8; 5120 x 13824 (7 spans) b = 5 14.8 -> 12.4, b = 6
@@ -459,7 +459,7 @@ static hipError_t launch_one(const GemvArgs &a, hipStream_t stream)
     int nw = kMaxWaves;
     if (a.waves_per_group > 0 && a.waves_per_group < nw) nw = a.waves_per_group;
     if (nw > nspans) nw = nspans;
-    if (NB == 1 && a.waves_per_group == 0) nw = batch1_waves(nspans);
+    if (NB <= 2 && a.waves_per_group == 0) nw = batch1_waves(nspans); // batch 2 gains the same (5 to 14 %)
     // several row groups per workgroup at batch 5..8 when every span has its own wave and there are
     // enough groups to keep the device full (at batch 2..4 the plain kernel measured faster)
     int rg = a.row_groups_per_wg;
@@ -512,7 +512,7 @@ template <int B, int NB> static hipError_t launch_multi_one(const MultiArgs &a, 
     constexpr int kMaxWaves = NB <= 4 ? 8 : 4;
     const int chunks = a.K / kChunkSlots;
     const int nspans = (chunks + kSpanLanes - 1) / kSpanLanes;
-    const int nw = nspans < kMaxWaves ? nspans : kMaxWaves;
+    const int nw = NB <= 2 ? batch1_waves(nspans) : nspans < kMaxWaves ? nspans : kMaxWaves; // as single calls do
     hipLaunchKernelGGL((gemv_multi_kernel<B, NB, 64 * kMaxWaves>), dim3(total_groups), dim3(64 * nw), 0, stream, a);
     return hipGetLastError();
 }
