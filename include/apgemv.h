@@ -204,7 +204,9 @@ ap_status ap_gemv_list(const ap_gemv_list_item *items, int count, void *stream);
 /*
  * The same work list for `batch` activation rows per item (1 <= batch <= 8): y_i (batch x M_i) =
  * x_i (batch x K_i) * W_i,b_i^T, the decode step of `batch` queries that run at the same precision
- * (Section 6.2 measures the kernel up to batch 8).  batch 1 is ap_gemv_list.  At batch >= 2 the items
+ * (Section 6.2 measures the kernel up to batch 8).  batch 1 is ap_gemv_list.  At batch 2 the items go into
+ * list launches of the kernel that single calls use at batch 1 and 2 (any shapes and bit-widths together, up
+ * to 32 per launch; bit-identical to separate ap_gemv calls).  At batch >= 3 the items
  * that the matrix-core kernel on tiles of 16 rows can take (K_i % 256 == 0) are launched together per
  * bit-width and class of row length, up to 32 per launch, whenever such a group has at least 1024 row
  * groups in total (the size rule of ap_gemv applied to the launch); every other item runs as its own

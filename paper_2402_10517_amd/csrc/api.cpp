@@ -252,7 +252,7 @@ extern "C" ap_status ap_gemv_list(const ap_gemv_list_item *items, int count, voi
         for (int i = 0; i < la.count; ++i)
             fill_list_item(items[first + i].h, items[first + i].b, items[first + i].x_dev, items[first + i].y_dev,
                            &la.item[i]);
-        if (launch_gemv_list(la, static_cast<hipStream_t>(stream)) != hipSuccess) return AP_ERR_HIP;
+        if (launch_gemv_list(la, 1, static_cast<hipStream_t>(stream)) != hipSuccess) return AP_ERR_HIP;
     }
     return AP_OK;
 }
@@ -266,6 +266,30 @@ extern "C" ap_status ap_gemv_list_batch(const ap_gemv_list_item *items, int coun
     for (int i = 0; i < count; ++i) { // every item is checked before anything is enqueued
         ap_status s = fill_list_item(items[i].h, items[i].b, items[i].x_dev, items[i].y_dev, &probe);
         if (s != AP_OK) return s;
+    }
+    if (batch == 2) {
+        // single calls at batch 2 run the batch-1/2 kernel: the items without a tuning override go into list
+        // launches of that kernel (any shapes and bit-widths together), the others run on their own
+        auto plain = [](const ap_matrix *h) {
+            return h->variant == AP_VARIANT_AUTO && h->waves_per_group == 0 && h->row_groups_per_wg < 0 && h->mfma_min_batch == 0;
+        };
+        ListArgs la;
+        std::memset(&la, 0, sizeof(la));
+        for (int i = 0; i < count; ++i) {
+            if (!plain(items[i].h)) continue;
+            fill_list_item(items[i].h, items[i].b, items[i].x_dev, items[i].y_dev, &la.item[la.count++]);
+            if (la.count == kMaxListItems) {
+                if (launch_gemv_list(la, 2, static_cast<hipStream_t>(stream)) != hipSuccess) return AP_ERR_HIP;
+                la.count = 0;
+            }
+        }
+        if (la.count > 0 && launch_gemv_list(la, 2, static_cast<hipStream_t>(stream)) != hipSuccess) return AP_ERR_HIP;
+        for (int i = 0; i < count; ++i) {
+            if (plain(items[i].h)) continue;
+            ap_status s = ap_gemv(items[i].h, items[i].b, items[i].x_dev, items[i].y_dev, batch, stream);
+            if (s != AP_OK) return s;
+        }
+        return AP_OK;
     }
     // Groups of items the tile kernel takes together: same bit-width, same class of row length; an item
     // whose handle carries a tuning override runs on its own.  Three passes over the list, no allocation.
@@ -325,7 +349,7 @@ extern "C" ap_status ap_gemv_multi(const ap_gemv_item *items, int count, int b, 
             ap_status s = fill_list_item(items[i].h, b, items[i].x_dev, items[i].y_dev, &la.item[i]);
             if (s != AP_OK) return s;
         }
-        return launch_gemv_list(la, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
+        return launch_gemv_list(la, 1, static_cast<hipStream_t>(stream)) == hipSuccess ? AP_OK : AP_ERR_HIP;
     }
     MultiArgs m;
     std::memset(&m, 0, sizeof(m));

@@ -247,8 +247,8 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, 6))) vo
 // gemv_kernel with the same number of waves, so every output is bit-identical to a separate call.
 // B = the bit-width of every item, or 0 for a list of mixed bit-widths (one kernel then holds all six
 // code paths and the registers of the widest; lists of one bit-width get that bit-width's own kernel).
-template <int B, int MAXT>
-__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, (B == 3 || B == 4) ? 8 : 6))) void gemv_list_kernel(ListArgs a)
+template <int B, int NB, int MAXT>
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, ((B == 3 || B == 4) && NB == 1) ? 8 : 6))) void gemv_list_kernel(ListArgs a)
 {
     int it = 0;
 #pragma unroll
@@ -262,21 +262,21 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2, (B == 3
     if ((int)(threadIdx.x >> 6) >= nwaves) return;
     const int g = (int)blockIdx.x - a.group_begin[it];
     if constexpr (B != 0) {
-        gemv_group<B, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves);
+        gemv_group<B, NB, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, NB, g, nwaves);
     } else {
         switch (I.b) {
-        case 3: gemv_group<3, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves); break;
-        case 4: gemv_group<4, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves); break;
-        case 5: gemv_group<5, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves); break;
-        case 6: gemv_group<6, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves); break;
-        case 7: gemv_group<7, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves); break;
-        default: gemv_group<8, 1, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, 1, g, nwaves); break;
+        case 3: gemv_group<3, NB, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, NB, g, nwaves); break;
+        case 4: gemv_group<4, NB, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, NB, g, nwaves); break;
+        case 5: gemv_group<5, NB, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, NB, g, nwaves); break;
+        case 6: gemv_group<6, NB, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, NB, g, nwaves); break;
+        case 7: gemv_group<7, NB, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, NB, g, nwaves); break;
+        default: gemv_group<8, NB, MAXT>(I.slices, I.slice_bytes, I.lut, I.x, I.y, I.M, K, NB, g, nwaves); break;
         }
     }
 }
 
 // One launch for the items of `a` whose rows need `nw` waves.
-static hipError_t launch_list_class(const ListArgs &a, int nw, hipStream_t stream)
+template <int NB> static hipError_t launch_list_class(const ListArgs &a, int nw, hipStream_t stream)
 {
     constexpr int kMaxWaves = 8;
     constexpr int T = 64 * kMaxWaves;
@@ -298,29 +298,30 @@ static hipError_t launch_list_class(const ListArgs &a, int nw, hipStream_t strea
     for (int i = sub.count; i < kMaxListItems; ++i) sub.group_begin[i] = 0x7fffffff;
     const dim3 grid(total), block(64 * max_nw);
     switch (b) {
-    case 3: hipLaunchKernelGGL((gemv_list_kernel<3, T>), grid, block, 0, stream, sub); break;
-    case 4: hipLaunchKernelGGL((gemv_list_kernel<4, T>), grid, block, 0, stream, sub); break;
-    case 5: hipLaunchKernelGGL((gemv_list_kernel<5, T>), grid, block, 0, stream, sub); break;
-    case 6: hipLaunchKernelGGL((gemv_list_kernel<6, T>), grid, block, 0, stream, sub); break;
-    case 7: hipLaunchKernelGGL((gemv_list_kernel<7, T>), grid, block, 0, stream, sub); break;
-    case 8: hipLaunchKernelGGL((gemv_list_kernel<8, T>), grid, block, 0, stream, sub); break;
-    default: hipLaunchKernelGGL((gemv_list_kernel<0, T>), grid, block, 0, stream, sub); break;
+    case 3: hipLaunchKernelGGL((gemv_list_kernel<3, NB, T>), grid, block, 0, stream, sub); break;
+    case 4: hipLaunchKernelGGL((gemv_list_kernel<4, NB, T>), grid, block, 0, stream, sub); break;
+    case 5: hipLaunchKernelGGL((gemv_list_kernel<5, NB, T>), grid, block, 0, stream, sub); break;
+    case 6: hipLaunchKernelGGL((gemv_list_kernel<6, NB, T>), grid, block, 0, stream, sub); break;
+    case 7: hipLaunchKernelGGL((gemv_list_kernel<7, NB, T>), grid, block, 0, stream, sub); break;
+    case 8: hipLaunchKernelGGL((gemv_list_kernel<8, NB, T>), grid, block, 0, stream, sub); break;
+    default: hipLaunchKernelGGL((gemv_list_kernel<0, NB, T>), grid, block, 0, stream, sub); break;
     }
     return hipGetLastError();
 }
 
-// The caller has checked every item (batch 1, 3 <= b <= 8).  Items are launched together per number of
-// waves their rows need (a workgroup has one wave per span, at most 8): a workgroup sized for the
-// longest row would hold wave slots for short rows that retire at once.
-hipError_t launch_gemv_list(ListArgs &a, hipStream_t stream)
+// The caller has checked every item (3 <= b <= 8; every item at batch `batch`, 1 or 2).  Items are launched
+// together per number of waves their rows take (batch1_waves): a workgroup sized for the longest row would hold
+// wave slots for short rows that retire at once.
+hipError_t launch_gemv_list(ListArgs &a, int batch, hipStream_t stream)
 {
+    if (batch != 1 && batch != 2) return hipErrorInvalidValue;
     bool seen[9] = {};
     for (int i = 0; i < a.count; ++i) {
         const int spans = (a.item[i].K / kChunkSlots + kSpanLanes - 1) / kSpanLanes;
         const int w = batch1_waves(spans);
         if (seen[w]) continue;
         seen[w] = true;
-        const hipError_t e = launch_list_class(a, w, stream);
+        const hipError_t e = batch == 1 ? launch_list_class<1>(a, w, stream) : launch_list_class<2>(a, w, stream);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

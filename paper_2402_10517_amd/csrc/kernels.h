@@ -56,7 +56,8 @@ struct ListArgs {
 };
 
 hipError_t launch_gemv(const GemvArgs &a, hipStream_t stream);
-hipError_t launch_gemv_list(ListArgs &a, hipStream_t stream);
+// a work list on the batch-1/2 kernel: every item at batch `batch` (1 or 2); group_begin is filled in there
+hipError_t launch_gemv_list(ListArgs &a, int batch, hipStream_t stream);
 hipError_t launch_gemv_multi(const MultiArgs &a, int b, int total_groups, hipStream_t stream);
 // the same launch on the matrix-core kernel over tiles of 16 rows (batch 2..8, K % 256 == 0)
 hipError_t launch_matrix_tile_multi(const MultiArgs &a, int b, hipStream_t stream);

@@ -25,7 +25,7 @@ hipError_t launch_gemv(const GemvArgs &, hipStream_t) { return hipErrorInvalidVa
 hipError_t launch_gemv_multi(const MultiArgs &, int, int, hipStream_t) { return hipErrorInvalidValue; }
 hipError_t launch_matrix_tile_multi(const MultiArgs &, int, hipStream_t) { return hipErrorInvalidValue; }
 hipError_t launch_matrix_tile_list(ListArgs &, int, int, hipStream_t) { return hipErrorInvalidValue; }
-hipError_t launch_gemv_list(ListArgs &, hipStream_t) { return hipErrorInvalidValue; }
+hipError_t launch_gemv_list(ListArgs &, int, hipStream_t) { return hipErrorInvalidValue; }
 hipError_t launch_dequantize(const GemvArgs &, hipStream_t) { return hipErrorInvalidValue; }
 hipError_t launch_probe_read(const void *, size_t, hipStream_t) { return hipErrorInvalidValue; }
 hipError_t launch_probe_issue(int, int, hipStream_t) { return hipErrorInvalidValue; }

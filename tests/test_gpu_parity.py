@@ -380,16 +380,24 @@ def test_batched_work_list(B, batch):
         assert np.all(out[:guard] == -5.0) and np.all(out[-guard:] == -5.0)
         y = out[guard:-guard].reshape(batch, pm.M)
         check_against_oracle(y, idx, luts[b], b, x)
-    # the first two items of the first half (b = 3, 2048 and 2304 columns: 1038 row groups together) ran on
-    # the tile kernel with 4 waves per tile, like a single call on it
-    for k in (0, 1):
-        idx, luts, x, pm, xd, b = meta[k]
-        pm.set_options(variant=B.VARIANT_TILE)
-        sep = B.ap_gemv(pm, b, xd)
-        torch.cuda.synchronize()
-        assert np.array_equal(bufs[k].cpu().numpy()[guard:-guard].reshape(batch, pm.M).view(np.uint16),
-                              sep.cpu().numpy().view(np.uint16))
-        pm.set_options(variant=B.VARIANT_AUTO)
+    if batch == 2:
+        # batch 2: every item ran in a list launch of the kernel that single calls use, bit for bit
+        for k, (idx, luts, x, pm, xd, b) in enumerate(meta):
+            sep = B.ap_gemv(pm, b, xd)
+            torch.cuda.synchronize()
+            assert np.array_equal(bufs[k].cpu().numpy()[guard:-guard].reshape(batch, pm.M).view(np.uint16),
+                                  sep.cpu().numpy().view(np.uint16))
+    else:
+        # the first two items of the first half (b = 3, 2048 and 2304 columns: 1038 row groups together) ran on
+        # the tile kernel with 4 waves per tile, like a single call on it
+        for k in (0, 1):
+            idx, luts, x, pm, xd, b = meta[k]
+            pm.set_options(variant=B.VARIANT_TILE)
+            sep = B.ap_gemv(pm, b, xd)
+            torch.cuda.synchronize()
+            assert np.array_equal(bufs[k].cpu().numpy()[guard:-guard].reshape(batch, pm.M).view(np.uint16),
+                                  sep.cpu().numpy().view(np.uint16))
+            pm.set_options(variant=B.VARIANT_AUTO)
     # argument checks: status of the first bad item, nothing enqueued; batch range
     bad = list(quads)
     bad[3] = (quads[3][0], 5, quads[3][2], quads[3][3])       # no table for b = 5
