@@ -514,7 +514,7 @@ def main():
     del big
     torch.cuda.empty_cache()
     if args.issue == "list":
-        kernel = "gemv_list_kernel<0,512>"   # template argument 0 = list of mixed bit-widths
+        kernel = "gemv_list_kernel<0,1,512>"   # template arguments: 0 = list of mixed bit-widths, 1 = batch 1
         dom_bytes, dom_us = step_bytes // list_launches, list_us / list_launches
     else:
         by_b = {}
