@@ -389,6 +389,75 @@ __device__ __forceinline__ void merge_words_pair4(const uint32_t (&q)[4], uint32
 __device__ __forceinline__ constexpr int pair4_even(int p) { return ((p >> 3) & 8) | ((p >> 2) & 4) | ((p << 1) & 2) | ((p >> 2) & 1); }
 __device__ __forceinline__ constexpr int pair4_odd(int p) { return ((p >> 4) & 8) | ((p >> 3) & 4) | (p & 2) | ((p >> 3) & 1); }
 
+// A ragged last span of at most 32 chunks on all 64 lanes (b = 4, 5, 6): lane l works on chunk l % 32 and on
+// two of its four rows, rows {0, 2} for l < 32 and {1, 3} for l >= 32, so the span costs half a wave-unit
+// instead of a whole one with half of the lanes idle (rows of 5120 columns: 2.5 instead of 3 units, 11008
+// columns: 5.4 instead of 6).  A row's table is 128 bytes at these bit-widths and bit 7 of an index byte is not
+// an index bit: it takes the lane's half, which puts the odd rows' tables one row further without an operation
+// per lookup (the even row 2 s is an immediate offset).  Per row, the products are added in the order of
+// compute_unit, into the accumulator of the row this lane works on.
+template <int B> constexpr bool half_unit_ok() { return B >= 4 && B <= 6; }
+template <int B, int NB>
+__device__ __forceinline__ void compute_unit_half(const u32x4 (&Q)[B], const u32x4 (&X)[NB][4], const uint8_t *tab,
+                                                  float (&acc)[NB][kRowsPerGroup], bool upper)
+{
+    using T = Table<B>;
+    constexpr int TB = T::kRowBytes;
+    static_assert(TB == 128 && (T::addr_mask() & 0x80u) == 0, "bit 7 of an index byte is free and selects the next row");
+    const uint32_t rowbit = upper ? 0x80808080u : 0u;
+    uint32_t one = 1;
+    asm("" : "+v"(one));
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const uint8_t *trow = tab + 2 * s * TB;
+        uint32_t q[B];
+#pragma unroll
+        for (int sl = 0; sl < B; ++sl) q[sl] = upper ? Q[sl][2 * s + 1] : Q[sl][2 * s];
+        uint32_t W[8];
+        merge_words<B>(q, W);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) W[u] = bitsel(0x80808080u, rowbit, W[u]);
+        float a[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) a[nb] = upper ? acc[nb][2 * s + 1] : acc[nb][2 * s];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            uint32_t ad[2][4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t v = W[2 * t + h];
+                ad[h][0] = byte_and<0>(v, T::addr_mask() | 0x80u);
+                ad[h][1] = byte_and<1>(v, T::addr_mask() | 0x80u);
+                ad[h][2] = byte_and<2>(v, T::addr_mask() | 0x80u);
+                ad[h][3] = byte_and<3>(v, T::addr_mask() | 0x80u);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint16_t w0 = *reinterpret_cast<const uint16_t *>(trow + ad[0][j]);
+                const uint16_t w1 = *reinterpret_cast<const uint16_t *>(trow + ad[1][j]);
+                if constexpr (NB == 1) {
+                    const uint32_t xw = X[0][t][j];
+                    const half2_t xp = __builtin_bit_cast(half2_t, xw);
+                    a[0] = __builtin_fmaf((float)__builtin_bit_cast(_Float16, w0), (float)xp.x, a[0]);
+                    a[0] = __builtin_fmaf((float)__builtin_bit_cast(_Float16, w1), (float)xp.y, a[0]);
+                } else {
+                    const uint32_t wp = (uint32_t)w0 | ((uint32_t)w1 << 16);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const uint32_t xw = X[nb][t][j];
+                        a[nb] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, wp), __builtin_bit_cast(half2_t, xw), a[nb], false);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            acc[nb][2 * s] = upper ? acc[nb][2 * s] : a[nb];
+            acc[nb][2 * s + 1] = upper ? a[nb] : acc[nb][2 * s + 1];
+        }
+    }
+}
+
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));

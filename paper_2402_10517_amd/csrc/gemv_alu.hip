@@ -63,12 +63,16 @@ __device__ __forceinline__ void gemv_group(const uint8_t *__restrict__ slices, s
     // format limits a matrix to 2^32 weights).
     const __amdgpu_buffer_rsrc_t srsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(slices + (size_t)g * chunks * 16), 0, 0xffffffffu, kBufferRsrcWord3);
+    // A ragged last span of at most 32 chunks runs on both halves of the wave at b = 4, 5, 6 (compute_unit_half):
+    // lane l then takes chunk l % 32.
+    auto halved = [&](int span) { return half_unit_ok<B>() && chunks - span * kSpanLanes <= 32; };
     auto issue_loads = [&](int span) {
         const int rem = chunks - span * kSpanLanes;
         const int nl = rem < kSpanLanes ? rem : kSpanLanes;
         // Lanes past the end of a ragged last span load what the last valid lane loads (and are
         // masked out of the compute): no branch around the loads.
-        const uint32_t loff = (uint32_t)(lane < nl ? lane : nl - 1) * 16u;
+        const int cl = halved(span) ? (lane & 31) : lane;
+        const uint32_t loff = (uint32_t)(cl < nl ? cl : nl - 1) * 16u;
         const uint32_t sspan = (uint32_t)span * (kSpanLanes * 16u);
 #pragma unroll
         for (int s = 0; s < B; ++s)
@@ -83,7 +87,7 @@ __device__ __forceinline__ void gemv_group(const uint8_t *__restrict__ slices, s
                 X[nb][t] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, loff, (uint32_t)(t * 16 * nl), 0);
         }
     };
-    auto active = [&](int span) { return lane < chunks - span * kSpanLanes; };
+    auto active = [&](int span) { return (halved(span) ? (lane & 31) : lane) < chunks - span * kSpanLanes; };
 
     float acc[NB][kRowsPerGroup];
 #pragma unroll
@@ -104,7 +108,11 @@ __device__ __forceinline__ void gemv_group(const uint8_t *__restrict__ slices, s
     stage_tables_store<B>(st, tab, nat, nwaves * 64); // waits for the table loads only
     __syncthreads();
     while (true) {
-        if (active(span)) compute_unit<B, NB>(Q, X, tab, acc);
+        if constexpr (half_unit_ok<B>()) {
+            if (halved(span)) {
+                if (active(span)) compute_unit_half<B, NB>(Q, X, tab, acc, lane >= 32);
+            } else if (active(span)) compute_unit<B, NB>(Q, X, tab, acc);
+        } else if (active(span)) compute_unit<B, NB>(Q, X, tab, acc);
         span += nwaves;
         if (span >= nspans) break;
         issue_loads(span);

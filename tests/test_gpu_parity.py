@@ -264,14 +264,19 @@ def test_bank_per_lane_variant(B, b):
 def test_two_row_groups_per_workgroup_variant(B, b):
     # forced (the dispatcher uses it on large matrices only): 2..8 spans, a ragged last span, an odd
     # number of row groups (the last workgroup holds one group), rows not a multiple of 4; the outputs
-    # are bit-identical to the kernel with one group per workgroup
+    # are bit-identical to the kernel with one group per workgroup, except where that kernel runs a ragged
+    # last span of at most 32 chunks on both halves of the wave (b = 4, 5, 6), which this variant does not
     for (M, K) in [(70, 2048 + 160), (129, 4096 + 32), (66, 3 * 2048), (10, 5 * 2048 + 736), (4, 8 * 2048), (37, 2048 + 32)]:
         idx, luts, x = inputs.make_case(26, M, K, bit_widths=[b])
         pm = B.ap_pack(idx, luts).set_options(variant=B.VARIANT_PAIR)
         y = run_gemv(pm, b, x)
         check_against_oracle(y, idx, luts[b], b, x)
         pm.set_options(variant=B.VARIANT_NO_PAIR)
-        assert np.array_equal(y.view(np.uint16), run_gemv(pm, b, x).view(np.uint16))
+        y1 = run_gemv(pm, b, x)
+        check_against_oracle(y1, idx, luts[b], b, x)
+        ragged = (K // 32) % 64
+        if not (b in (4, 5, 6) and 0 < ragged <= 32):
+            assert np.array_equal(y.view(np.uint16), y1.view(np.uint16))
         pm.close()
 
 
